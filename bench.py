@@ -1,0 +1,159 @@
+"""Benchmark of the whole self-attention call on one MI355X.
+
+One step = one attn_forward: weight re-layout, q/k/v projection GEMM and the
+fused score/softmax/weighted-sum kernel with redundancy skipping, on synthetic
+inputs already resident in HBM.  Prints ONE JSON line.
+
+  value     useful TFLOP/s of the whole call: (projection FLOPs + 4*d_k FLOPs per
+            NEEDED pair, i.e. post-skip) / wall time per step
+  roofline  the dominant kernel (by time) against the bf16 MFMA peak; its
+            duration is measured with HIP events recorded by the library on the
+            launch stream around every kernel of the timed steps
+  cpu_baseline  the float64 CPU checker timed on a bounded sample of the same
+            workload (reported, not a target)
+"""
+from __future__ import annotations
+
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+MFMA_BF16_PEAK_TFLOPS = 2500.0   # MI355X dense bf16, published
+METRIC = "useful attention TFLOP/s (post-skip) + % bf16 MFMA peak, 1 MI355X"
+
+
+def needed_pairs(w, lens):
+    """Pairs phase 1 must touch, all batch items and heads (closed forms)."""
+    n = w.n
+    from paper_2012_01114_amd import inputs
+    if w.scheme == inputs.SCHEME_CAUSAL:
+        per = [int(L) * (int(L) + 1) // 2 + (n - int(L)) * int(L) for L in (lens if lens is not None else [n] * w.batch)]
+    else:
+        per = [n * int(L) for L in (lens if lens is not None else [n] * w.batch)]
+    return sum(per) * w.n_heads
+
+
+def cpu_baseline(w, f64, lens, budget_heads):
+    """Time the CPU checker on `budget_heads` (batch, head) pairs, 256 sampled rows each."""
+    from oracle import attn_oracle as orc
+    import numpy as np
+    rng = np.random.default_rng(7)
+    t_total, flop = 0.0, 0.0
+    picks = []
+    for s in range(budget_heads):
+        b = int(rng.integers(0, w.batch))
+        h = int(rng.integers(0, w.n_heads))
+        rows = sorted(int(r) for r in rng.choice(w.n, size=min(256, w.n), replace=False))
+        t0 = time.perf_counter()
+        orc.head_rows(f64["X"], f64["Wq"], f64["Wk"], f64["Wv"], n_heads=w.n_heads, d_k=w.d_k, p=w.p,
+                      scheme=w.scheme, scale=w.d_k ** -0.5, b=b, h=h, rows=rows, lens=lens)
+        t_total += time.perf_counter() - t0
+        L = w.n if lens is None else int(lens[b])
+        from paper_2012_01114_amd import inputs
+        pairs = sum(min(r + 1, L) if w.scheme == inputs.SCHEME_CAUSAL else L for r in rows)
+        flop += 2.0 * w.d_model * w.d_k * (2 * w.n + len(rows)) + 4.0 * w.d_k * pairs
+        picks.append((b, h))
+    return {"value": flop / t_total / 1e12, "unit": "TFLOP/s", "cores": orc.num_threads(), "kind": "oracle",
+            "seconds": round(t_total, 2),
+            "sample": f"{budget_heads} (batch, head) pairs, k and v projected for all {w.n} rows, "
+                      f"{min(256, w.n)} random query rows each; FLOPs counted for the sample only"}
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=50)
+    ap.add_argument("--warmup", type=int, default=10)
+    ap.add_argument("--workload", default="long", help="tiny|encoder|causal|long|padded")
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    args = ap.parse_args()
+    if args.gpus != 1:
+        sys.exit("bench.py: this build runs on one GPU only (no collectives, no sharding); use --gpus 1")
+
+    import numpy as np
+    import torch
+    from paper_2012_01114_amd import attnring as ar
+    from paper_2012_01114_amd import inputs
+
+    if not torch.cuda.is_available():
+        sys.exit("bench.py: no GPU visible")
+    if not os.path.exists(ar.LIB_PATH):
+        from paper_2012_01114_amd import build as libbuild
+        libbuild.build()
+    w = inputs.WORKLOADS[args.workload]
+    stored, f64 = inputs.make_inputs(w)
+    lens = stored["lens"]
+    dev = torch.device("cuda:0")
+    X, Wq, Wk, Wv = [stored[k].to(dev) for k in ("X", "Wq", "Wk", "Wv")]
+    lens_dev = None if lens is None else torch.from_numpy(lens).to(dev)
+    out = torch.empty(w.batch, w.n, w.hd, dtype=X.dtype, device=dev)
+    dt = ar.ATTN_F32 if w.dtype == "f32" else ar.ATTN_BF16
+    ctx = ar.attn_init(w.batch, w.n, w.d_model, w.n_heads, w.d_k, w.p, dt, 0.0, 0)
+    ar.attn_set_key_lengths(ctx, lens_dev)
+    stream = torch.cuda.current_stream(dev)
+
+    for _ in range(args.warmup):
+        ar.attn_forward(ctx, X, Wq, Wk, Wv, w.scheme, out, stream)
+    torch.cuda.synchronize()
+
+    # timed region: exactly K steps; the library records HIP events around each kernel
+    ar.attn_profile(ctx, True)
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for _ in range(args.steps):
+        ar.attn_forward(ctx, X, Wq, Wk, Wv, w.scheme, out, stream)
+    torch.cuda.synchronize()
+    t1 = time.perf_counter()
+    prof = ar.attn_profile_read(ctx)
+    ar.attn_profile(ctx, False)
+    stats = ar.attn_stats(ctx)
+
+    ms_step = (t1 - t0) * 1e3 / args.steps
+    pairs = needed_pairs(w, lens)
+    assert pairs == stats["pairs_needed"][0], (pairs, stats["pairs_needed"])
+    attn_flop = 4.0 * w.d_k * pairs
+    proj_flop = 6.0 * w.batch * w.n * w.d_model * w.hd
+    value = (attn_flop + proj_flop) / (ms_step * 1e-3) / 1e12
+
+    kern = {
+        "attention": {"flop": attn_flop, "ms": prof["ms_attention"]},
+        "projection": {"flop": proj_flop, "ms": prof["ms_projection"]},
+    }
+    dom = max(kern, key=lambda k: kern[k]["ms"])
+    achieved = kern[dom]["flop"] / (kern[dom]["ms"] * 1e-3) / 1e12
+    roofline = {"kernel": dom, "bound": "mfma", "achieved": round(achieved, 2), "peak": MFMA_BF16_PEAK_TFLOPS,
+                "unit": "TFLOP/s", "frac": round(achieved / MFMA_BF16_PEAK_TFLOPS, 4), "traffic": None,
+                "avg_ms": round(kern[dom]["ms"], 4)}
+    extra = {k: {"tflops": round(v["flop"] / (v["ms"] * 1e-3) / 1e12, 2), "avg_ms": round(v["ms"], 4),
+                 "frac_of_mfma_peak": round(v["flop"] / (v["ms"] * 1e-3) / 1e12 / MFMA_BF16_PEAK_TFLOPS, 4)}
+             for k, v in kern.items()}
+    extra["prepare_avg_ms"] = round(prof["ms_prepare"], 4)
+
+    line = {
+        "metric": METRIC, "value": round(value, 2), "unit": "TFLOP/s", "n_gpus": 1, "steps": args.steps,
+        "warmup": args.warmup, "ms_per_step": round(ms_step, 4), "higher_is_better": True, "scaling": "weak",
+        "vs_baseline": None, "dtype": "bf16" if w.dtype == "bf16" else "f32", "data": "synthetic",
+        "pct_bf16_mfma_peak": round(100.0 * value / MFMA_BF16_PEAK_TFLOPS, 2),
+        "config": {"workload": f"{w.name}: batch {w.batch}, n {w.n}, d_model {w.d_model}, heads {w.n_heads}, "
+                               f"d_k {w.d_k}, scheme {inputs.SCHEME_NAMES[w.scheme]}, P {w.p}"
+                               + (", key lengths from seed" if lens is not None else ""),
+                   "needed_pairs": pairs, "full_pairs": stats["pairs_full"],
+                   "tiles_executed": stats["tiles_executed"], "tiles_full": stats["tiles_full"]},
+        "roofline": roofline,
+        "kernels": extra,
+    }
+    torch.cuda.synchronize()
+    ar.attn_destroy(ctx)
+    if not args.no_cpu_baseline:
+        line["cpu_baseline"] = cpu_baseline(w, f64, lens, budget_heads=8 if w.name == "long" else 16)
+    print(json.dumps(line))
+
+
+if __name__ == "__main__":
+    main()

@@ -1,0 +1,385 @@
+// Host side of libattnring.so: the C ABI declared in include/attnring.h.
+// Validation, workspace, choice of kernel path, launches, counters, timing.
+#include "../../include/attnring.h"
+
+#include <cmath>
+#include <cstdio>
+#include <cstring>
+#include <new>
+#include <vector>
+
+#include "common.h"
+
+using namespace attnring;
+
+struct attn_ctx {
+    attn_config cfg;
+    int device;
+    int b, Npad;
+    float scale;
+    bool mfma_shape;  // shape and dtype fit the bf16 MFMA kernels
+    // bf16 MFMA workspace
+    bf16_t *qb, *kb, *vtb, *wt;
+    // generic float workspace (allocated on first use)
+    float *qf, *kf, *vf;
+    float* scores;  // q = k = v scheme: one n x n score matrix per (batch, head)
+    unsigned long long* counters;
+    const int32_t* lens;
+    // last forward
+    hipStream_t last_stream;
+    int last_scheme;
+    int last_proj_gemms;
+    int last_phys;
+    bool have_forward;
+    // timing
+    bool prof_on;
+    int prof_calls;
+    std::vector<hipEvent_t> events;  // 4 per timed call
+    char err[512];
+};
+
+namespace {
+
+thread_local char g_init_err[512] = "";
+constexpr int MAX_PROFILE_CALLS = 4096;
+constexpr size_t MAX_SCORE_BYTES = (size_t)1 << 30;
+
+attn_status fail(attn_ctx* ctx, attn_status st, const char* fmt, const char* detail = "")
+{
+    char* dst = ctx ? ctx->err : g_init_err;
+    snprintf(dst, 512, fmt, detail);
+    return st;
+}
+
+attn_status hip_fail(attn_ctx* ctx, const char* what, hipError_t e)
+{
+    char* dst = ctx ? ctx->err : g_init_err;
+    snprintf(dst, 512, "%s: %s", what, hipGetErrorString(e));
+    return e == hipErrorOutOfMemory ? ATTN_ERR_ALLOC : ATTN_ERR_DEVICE;
+}
+
+void free_all(attn_ctx* c)
+{
+    void* ptrs[] = {c->qb, c->kb, c->vtb, c->wt, c->qf, c->kf, c->vf, c->scores, c->counters};
+    for (void* p : ptrs)
+        if (p) (void)hipFree(p);
+    for (hipEvent_t e : c->events) (void)hipEventDestroy(e);
+    c->events.clear();
+}
+
+Problem make_problem(const attn_ctx* c, int scheme)
+{
+    Problem pb;
+    pb.B = c->cfg.batch; pb.N = c->cfg.n; pb.D = c->cfg.d_model; pb.H = c->cfg.n_heads; pb.d = c->cfg.d_k;
+    pb.P = c->cfg.p; pb.b = c->b; pb.Npad = c->Npad; pb.scale = c->scale; pb.scheme = scheme;
+    pb.noskip = (c->cfg.flags & ATTN_FLAG_NO_SKIP) != 0;
+    pb.is_bf16 = c->cfg.dtype == ATTN_BF16;
+    pb.lens = c->lens;
+    pb.counters = c->counters;
+    return pb;
+}
+
+__global__ void zero_counters_kernel(unsigned long long* c)
+{
+    if (threadIdx.x < CNT_WORDS) c[threadIdx.x] = 0ull;
+}
+
+attn_status ensure_generic_workspace(attn_ctx* c)
+{
+    if (c->qf) return ATTN_OK;
+    const size_t bytes = (size_t)c->cfg.batch * c->cfg.n_heads * c->cfg.n * c->cfg.d_k * sizeof(float);
+    float** dst[3] = {&c->qf, &c->kf, &c->vf};
+    for (auto p : dst) {
+        hipError_t e = hipMalloc((void**)p, bytes);
+        if (e != hipSuccess) return hip_fail(c, "hipMalloc(float q/k/v workspace)", e);
+    }
+    return ATTN_OK;
+}
+
+bool aligned_to(const void* p, size_t a) { return (reinterpret_cast<uintptr_t>(p) & (a - 1)) == 0; }
+
+// sum over batch items of f(len_b), key lengths copied from the device when set
+template <typename F>
+attn_status sum_over_lengths(attn_ctx* c, F f, unsigned long long* out)
+{
+    const int B = c->cfg.batch, N = c->cfg.n;
+    std::vector<int32_t> lens((size_t)B, N);
+    if (c->lens) {
+        hipError_t e = hipMemcpy(lens.data(), c->lens, sizeof(int32_t) * (size_t)B, hipMemcpyDeviceToHost);
+        if (e != hipSuccess) return hip_fail(c, "hipMemcpy(key lengths)", e);
+    }
+    unsigned long long s = 0;
+    for (int b = 0; b < B; ++b) {
+        long long L = lens[(size_t)b];
+        L = L < 0 ? 0 : (L > N ? N : L);
+        s += f((unsigned long long)L);
+    }
+    *out = s;
+    return ATTN_OK;
+}
+
+}  // namespace
+
+extern "C" {
+
+attn_status attn_init(const attn_config* cfg, attn_ctx** out_ctx)
+{
+    if (out_ctx) *out_ctx = nullptr;
+    if (!cfg || !out_ctx) return fail(nullptr, ATTN_ERR_INVALID, "attn_init: NULL argument%s");
+    if (cfg->batch < 1 || cfg->n < 1 || cfg->d_model < 1 || cfg->n_heads < 1 || cfg->d_k < 1 || cfg->p < 1)
+        return fail(nullptr, ATTN_ERR_INVALID, "attn_init: every size must be >= 1%s");
+    if (cfg->dtype != ATTN_F32 && cfg->dtype != ATTN_BF16)
+        return fail(nullptr, ATTN_ERR_INVALID, "attn_init: unknown dtype%s");
+    if (cfg->flags & ~(uint32_t)ATTN_FLAG_NO_SKIP) return fail(nullptr, ATTN_ERR_INVALID, "attn_init: unknown flag%s");
+    if (!(cfg->scale == cfg->scale) || std::isinf(cfg->scale))
+        return fail(nullptr, ATTN_ERR_INVALID, "attn_init: scale is not finite%s");
+    if (cfg->n % cfg->p != 0)
+        return fail(nullptr, ATTN_ERR_SHAPE, "attn_init: n must be divisible by p (ring partitions)%s");
+    const long long Npad = ((long long)cfg->n + 127) / 128 * 128;
+    const long long hd = (long long)cfg->n_heads * cfg->d_k;
+    const long long limit = 0x7fffffffLL;
+    if ((long long)cfg->batch * Npad * hd > limit || (long long)cfg->batch * cfg->n * cfg->d_model > limit ||
+        3 * hd * cfg->d_model > limit || (long long)cfg->p * cfg->p > limit)
+        return fail(nullptr, ATTN_ERR_SHAPE, "attn_init: problem too large for 32-bit element indices%s");
+    if (cfg->d_k > 256)
+        return fail(nullptr, ATTN_ERR_UNSUPPORTED, "attn_init: d_k above 256 is not implemented%s");
+
+    attn_ctx* c = new (std::nothrow) attn_ctx();
+    if (!c) return fail(nullptr, ATTN_ERR_ALLOC, "attn_init: out of host memory%s");
+    c->cfg = *cfg;
+    c->b = cfg->n / cfg->p;
+    c->Npad = (int)Npad;
+    c->scale = cfg->scale == 0.f ? 1.f / std::sqrt((float)cfg->d_k) : cfg->scale;
+    c->err[0] = 0;
+    hipError_t e = hipGetDevice(&c->device);
+    if (e != hipSuccess) { attn_status st = hip_fail(nullptr, "hipGetDevice", e); delete c; return st; }
+
+    c->mfma_shape = cfg->dtype == ATTN_BF16 && (cfg->d_k == 64 || cfg->d_k == 128) && cfg->d_model % 8 == 0 &&
+                    c->scale > 0.f;
+    e = hipMalloc((void**)&c->counters, sizeof(unsigned long long) * CNT_WORDS);
+    if (e == hipSuccess) e = hipMemset(c->counters, 0, sizeof(unsigned long long) * CNT_WORDS);
+    if (e == hipSuccess && c->mfma_shape) {
+        const size_t qkv = (size_t)cfg->batch * c->Npad * hd * sizeof(bf16_t);
+        bf16_t** dst[3] = {&c->qb, &c->kb, &c->vtb};
+        for (auto p : dst) {
+            if (e == hipSuccess) e = hipMalloc((void**)p, qkv);
+            if (e == hipSuccess) e = hipMemset(*p, 0, qkv);  // rows past n stay zero for good
+        }
+        if (e == hipSuccess) e = hipMalloc((void**)&c->wt, (size_t)3 * hd * cfg->d_model * sizeof(bf16_t));
+    }
+    if (e == hipSuccess) e = hipDeviceSynchronize();
+    if (e != hipSuccess) {
+        attn_status st = hip_fail(nullptr, "attn_init: workspace", e);
+        free_all(c);
+        delete c;
+        return st;
+    }
+    if (!c->mfma_shape) {
+        attn_status st = ensure_generic_workspace(c);
+        if (st != ATTN_OK) {
+            snprintf(g_init_err, sizeof(g_init_err), "%s", c->err);
+            free_all(c);
+            delete c;
+            return st;
+        }
+    }
+    *out_ctx = c;
+    return ATTN_OK;
+}
+
+attn_status attn_set_key_lengths(attn_ctx* ctx, const int32_t* lens_dev)
+{
+    if (!ctx) return fail(nullptr, ATTN_ERR_INVALID, "attn_set_key_lengths: NULL context%s");
+    ctx->lens = lens_dev;
+    return ATTN_OK;
+}
+
+attn_status attn_forward(attn_ctx* ctx, const void* X, const void* Wq, const void* Wk, const void* Wv,
+                         int32_t scheme, void* out, void* hip_stream)
+{
+    if (!ctx) return fail(nullptr, ATTN_ERR_INVALID, "attn_forward: NULL context%s");
+    if (!X || !out) return fail(ctx, ATTN_ERR_INVALID, "attn_forward: X and out must not be NULL%s");
+    if (scheme != ATTN_SCHEME_FULL && scheme != ATTN_SCHEME_SYMMETRIC && scheme != ATTN_SCHEME_CAUSAL)
+        return fail(ctx, ATTN_ERR_INVALID, "attn_forward: unknown scheme%s");
+    const attn_config& cf = ctx->cfg;
+    const int hd = cf.n_heads * cf.d_k;
+    if (scheme == ATTN_SCHEME_SYMMETRIC) {
+        if (ctx->lens) return fail(ctx, ATTN_ERR_UNSUPPORTED, "attn_forward: key lengths with the q=k=v scheme%s");
+        if (!Wq && cf.d_model != hd)
+            return fail(ctx, ATTN_ERR_INVALID, "attn_forward: Wq == NULL needs d_model == n_heads*d_k%s");
+        if (cf.d_k > 256) return fail(ctx, ATTN_ERR_UNSUPPORTED, "attn_forward: q=k=v scheme with d_k above 256%s");
+    } else if (!Wq || !Wk || !Wv) {
+        return fail(ctx, ATTN_ERR_INVALID, "attn_forward: Wq, Wk and Wv must not be NULL%s");
+    }
+    hipStream_t s = (hipStream_t)hip_stream;
+    Problem pb = make_problem(ctx, scheme);
+    hipError_t e;
+
+    hipEvent_t* ev = nullptr;
+    if (ctx->prof_on && ctx->prof_calls < MAX_PROFILE_CALLS) {
+        const size_t need = (size_t)(ctx->prof_calls + 1) * 4;
+        while (ctx->events.size() < need) {
+            hipEvent_t n;
+            e = hipEventCreate(&n);
+            if (e != hipSuccess) return hip_fail(ctx, "hipEventCreate", e);
+            ctx->events.push_back(n);
+        }
+        ev = &ctx->events[(size_t)ctx->prof_calls * 4];
+    }
+#define MARK(i_)                                                              \
+    if (ev) {                                                                 \
+        e = hipEventRecord(ev[i_], s);                                        \
+        if (e != hipSuccess) return hip_fail(ctx, "hipEventRecord", e);       \
+    }
+#define CHECK(what_)                                                          \
+    if (e != hipSuccess) return hip_fail(ctx, what_, e);
+
+    MARK(0);
+    hipLaunchKernelGGL(zero_counters_kernel, dim3(1), dim3(64), 0, s, ctx->counters);
+    e = hipGetLastError();
+    CHECK("launch zero_counters");
+
+    const bool use_mfma = ctx->mfma_shape && scheme != ATTN_SCHEME_SYMMETRIC && aligned_to(X, 16) &&
+                          aligned_to(out, 8) && aligned_to(Wq, 2) && aligned_to(Wk, 2) && aligned_to(Wv, 2);
+    if (use_mfma) {
+        e = launch_transpose_w(pb, (const bf16_t*)Wq, (const bf16_t*)Wk, (const bf16_t*)Wv, ctx->wt, s);
+        CHECK("launch transpose_w");
+        MARK(1);
+        e = launch_proj_mfma(pb, (const bf16_t*)X, ctx->wt, ctx->qb, ctx->kb, ctx->vtb, s);
+        CHECK("launch proj_mfma");
+        MARK(2);
+        e = launch_attn_mfma(pb, ctx->qb, ctx->kb, ctx->vtb, (bf16_t*)out, s);
+        CHECK("launch attn_mfma");
+        MARK(3);
+        ctx->last_proj_gemms = 3;
+        ctx->last_phys = MFMA_BLOCK;
+    } else {
+        attn_status st = ensure_generic_workspace(ctx);
+        if (st != ATTN_OK) return st;
+        MARK(1);
+        if (scheme == ATTN_SCHEME_SYMMETRIC) {
+            const size_t bytes = (size_t)cf.batch * cf.n_heads * cf.n * cf.n * sizeof(float);
+            if (bytes > MAX_SCORE_BYTES)
+                return fail(ctx, ATTN_ERR_UNSUPPORTED, "attn_forward: q=k=v score scratch would exceed 1 GiB%s");
+            if (!ctx->scores) {
+                e = hipMalloc((void**)&ctx->scores, bytes);
+                CHECK("hipMalloc(score scratch)");
+            }
+            if (Wq) e = launch_proj_generic(pb, X, Wq, ctx->qf, s);
+            else e = launch_copy_heads_generic(pb, X, ctx->qf, s);
+            CHECK("launch projection (q=k=v)");
+            MARK(2);
+            e = launch_sym_generic(pb, ctx->qf, ctx->scores, out, s);
+            CHECK("launch q=k=v attention");
+            ctx->last_proj_gemms = Wq ? 1 : 0;
+        } else {
+            e = launch_proj_generic(pb, X, Wq, ctx->qf, s);
+            if (e == hipSuccess) e = launch_proj_generic(pb, X, Wk, ctx->kf, s);
+            if (e == hipSuccess) e = launch_proj_generic(pb, X, Wv, ctx->vf, s);
+            CHECK("launch projection");
+            MARK(2);
+            e = launch_attn_generic(pb, ctx->qf, ctx->kf, ctx->vf, out, s);
+            CHECK("launch attention");
+            ctx->last_proj_gemms = 3;
+        }
+        MARK(3);
+        ctx->last_phys = ctx->b;
+    }
+#undef MARK
+#undef CHECK
+    if (ev) ctx->prof_calls += 1;
+    ctx->last_stream = s;
+    ctx->last_scheme = scheme;
+    ctx->have_forward = true;
+    return ATTN_OK;
+}
+
+attn_status attn_stats(attn_ctx* ctx, attn_stats_t* out)
+{
+    if (!ctx) return fail(nullptr, ATTN_ERR_INVALID, "attn_stats: NULL context%s");
+    if (!out) return fail(ctx, ATTN_ERR_INVALID, "attn_stats: NULL output%s");
+    if (!ctx->have_forward) return fail(ctx, ATTN_ERR_INVALID, "attn_stats: no attn_forward has run%s");
+    hipError_t e = hipStreamSynchronize(ctx->last_stream);
+    if (e != hipSuccess) return hip_fail(ctx, "hipStreamSynchronize", e);
+    unsigned long long cnt[CNT_WORDS];
+    e = hipMemcpy(cnt, ctx->counters, sizeof(cnt), hipMemcpyDeviceToHost);
+    if (e != hipSuccess) return hip_fail(ctx, "hipMemcpy(counters)", e);
+
+    const attn_config& cf = ctx->cfg;
+    const unsigned long long n = (unsigned long long)cf.n, H = (unsigned long long)cf.n_heads;
+    const unsigned long long B = (unsigned long long)cf.batch, P = (unsigned long long)cf.p;
+    memset(out, 0, sizeof(*out));
+    out->pairs_full = B * H * n * n;
+    out->tiles_full = B * H * P * P;
+    attn_status st = ATTN_OK;
+    unsigned long long per_head_sum = 0;
+    switch (ctx->last_scheme) {
+    case ATTN_SCHEME_FULL:  // Sec. 3.2: n^2 per phase; with key padding n*len
+        st = sum_over_lengths(ctx, [n](unsigned long long L) { return n * L; }, &per_head_sum);
+        for (int ph = 0; ph < 3; ++ph) out->pairs_needed[ph] = out->pairs_scheduled[ph] = H * per_head_sum;
+        break;
+    case ATTN_SCHEME_SYMMETRIC:  // Sec. 4.1 / 4.2: phase 1 n(n+1)/2 needed, n(n+2)/2 scheduled for even n
+        out->pairs_needed[0] = B * H * (n * (n + 1) / 2);
+        out->pairs_scheduled[0] = B * H * ((n % 2) ? n * (n + 1) / 2 : n * (n + 2) / 2);
+        for (int ph = 1; ph < 3; ++ph) out->pairs_needed[ph] = out->pairs_scheduled[ph] = B * H * n * n;
+        break;
+    default:  // Sec. 5.1: n(n+1)/2 in all phases; with key padding sum_i min(i+1, len)
+        st = sum_over_lengths(
+            ctx, [n](unsigned long long L) { return L * (L + 1) / 2 + (n - L) * L; }, &per_head_sum);
+        for (int ph = 0; ph < 3; ++ph) out->pairs_needed[ph] = out->pairs_scheduled[ph] = H * per_head_sum;
+        break;
+    }
+    if (st != ATTN_OK) return st;
+    out->tiles_executed = cnt[CNT_LOGICAL];
+    out->pairs_executed = cnt[CNT_LOGICAL] * (unsigned long long)ctx->b * (unsigned long long)ctx->b;
+    out->phys_tiles_executed = cnt[CNT_PHYS];
+    out->phys_br = out->phys_bc = ctx->last_phys;
+    out->proj_gemms = (unsigned long long)ctx->last_proj_gemms;
+    return ATTN_OK;
+}
+
+attn_status attn_profile(attn_ctx* ctx, int32_t enable)
+{
+    if (!ctx) return fail(nullptr, ATTN_ERR_INVALID, "attn_profile: NULL context%s");
+    if (enable && ctx->have_forward) {
+        hipError_t e = hipStreamSynchronize(ctx->last_stream);  // events of the old record may be reused
+        if (e != hipSuccess) return hip_fail(ctx, "hipStreamSynchronize", e);
+    }
+    ctx->prof_on = enable != 0;
+    if (enable) ctx->prof_calls = 0;
+    return ATTN_OK;
+}
+
+attn_status attn_profile_read(attn_ctx* ctx, attn_profile_t* out)
+{
+    if (!ctx) return fail(nullptr, ATTN_ERR_INVALID, "attn_profile_read: NULL context%s");
+    if (!out) return fail(ctx, ATTN_ERR_INVALID, "attn_profile_read: NULL output%s");
+    memset(out, 0, sizeof(*out));
+    if (ctx->prof_calls == 0) return ATTN_OK;
+    hipError_t e = hipStreamSynchronize(ctx->last_stream);
+    if (e != hipSuccess) return hip_fail(ctx, "hipStreamSynchronize", e);
+    double sum[3] = {0, 0, 0};
+    for (int c = 0; c < ctx->prof_calls; ++c)
+        for (int k = 0; k < 3; ++k) {
+            float ms = 0.f;
+            e = hipEventElapsedTime(&ms, ctx->events[(size_t)c * 4 + k], ctx->events[(size_t)c * 4 + k + 1]);
+            if (e != hipSuccess) return hip_fail(ctx, "hipEventElapsedTime", e);
+            sum[k] += ms;
+        }
+    out->calls = ctx->prof_calls;
+    out->ms_prepare = (float)(sum[0] / ctx->prof_calls);
+    out->ms_projection = (float)(sum[1] / ctx->prof_calls);
+    out->ms_attention = (float)(sum[2] / ctx->prof_calls);
+    return ATTN_OK;
+}
+
+const char* attn_last_error(const attn_ctx* ctx) { return ctx ? ctx->err : g_init_err; }
+
+void attn_destroy(attn_ctx* ctx)
+{
+    if (!ctx) return;
+    free_all(ctx);
+    delete ctx;
+}
+
+}  // extern "C"

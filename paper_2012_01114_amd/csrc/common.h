@@ -1,0 +1,50 @@
+// Internal declarations shared by the translation units of libattnring.so.
+// Nothing here is part of the public C ABI (see include/attnring.h).
+#pragma once
+
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+namespace attnring {
+
+typedef unsigned short bf16_t;  // raw bfloat16 bits
+
+enum { SCHEME_FULL = 0, SCHEME_SYMMETRIC = 1, SCHEME_CAUSAL = 2 };
+
+// Everything a kernel launcher needs to know about one forward call.
+struct Problem {
+    int B, N, D, H, d;   // batch, vectors, d_model, heads, d_k
+    int P, b;            // ring partitions and rows per partition (b = N / P)
+    int Npad;            // row pitch of the projected bf16 q/k/v (multiple of 128)
+    float scale;         // multiplies the raw scores
+    int scheme;
+    bool noskip;         // debug: visit every tile, mask with -inf
+    bool is_bf16;        // storage type of X, W, out
+    const int* lens;     // device, [B] or nullptr
+    unsigned long long* counters;  // device: [0] logical tiles, [1] physical score blocks
+};
+
+// Device counters written by the attention kernels.
+enum { CNT_LOGICAL = 0, CNT_PHYS = 1, CNT_WORDS = 2 };
+
+// ---- generic float-compute path (any shape, f32 or bf16 storage) ----------
+// q/k/v workspace: float [B][H][N][d].
+hipError_t launch_proj_generic(const Problem& pb, const void* X, const void* W, float* out, hipStream_t s);
+hipError_t launch_copy_heads_generic(const Problem& pb, const void* X, float* out, hipStream_t s);
+hipError_t launch_attn_generic(const Problem& pb, const float* q, const float* k, const float* v,
+                               void* out, hipStream_t s);
+hipError_t launch_sym_generic(const Problem& pb, const float* z, float* scores, void* out, hipStream_t s);
+
+// ---- bf16 MFMA path (d_k 64 or 128, FULL and CAUSAL) -----------------------
+// Wt: [3][H*d][D] (transposed weights); q, k: [B][H][Npad][d]; vt: [B][H][d][Npad]
+// with the keys of every 16-block stored in MFMA operand order.
+hipError_t launch_transpose_w(const Problem& pb, const bf16_t* Wq, const bf16_t* Wk, const bf16_t* Wv,
+                              bf16_t* Wt, hipStream_t s);
+hipError_t launch_proj_mfma(const Problem& pb, const bf16_t* X, const bf16_t* Wt, bf16_t* q, bf16_t* k,
+                            bf16_t* vt, hipStream_t s);
+hipError_t launch_attn_mfma(const Problem& pb, const bf16_t* q, const bf16_t* k, const bf16_t* vt,
+                            bf16_t* out, hipStream_t s);
+// Physical score-block edge of the MFMA attention kernel (phys_br = phys_bc).
+enum { MFMA_BLOCK = 32 };
+
+}  // namespace attnring

@@ -1,0 +1,239 @@
+// q/k/v projections (Sec. 3.1: q, k, v are linear maps of the inputs x by three
+// learned matrices; one set per head) as ONE bf16 MFMA GEMM over the stacked
+// output columns [q | k | v], fp32 accumulation, written straight into the
+// layouts the attention kernel streams:
+//   q, k : [B][H][Npad][d]            (row = vector, d contiguous)
+//   v^T  : [B][H][Npad/64][d][64]     (per 64-key block, key contiguous, and the
+//                                      keys of each 16-group in MFMA operand order)
+// The weights arrive as [D][H*d] (q = x.W); a small kernel first lays them out
+// as W^T [3*H*d][D] so that both GEMM operands are contiguous along the
+// contraction index, which is what the MFMA operand registers want.
+#include "mfma_common.h"
+
+namespace attnring {
+namespace {
+
+// ---------------------------------------------------------------------------
+// W^T: 64 x 64 tiles through LDS; grid (HD/64, ceil(D/64), 3).
+// ---------------------------------------------------------------------------
+__global__ __launch_bounds__(256) void transpose_w_kernel(int D, int HD, const bf16_t* __restrict__ Wq,
+                                                          const bf16_t* __restrict__ Wk,
+                                                          const bf16_t* __restrict__ Wv, bf16_t* __restrict__ Wt)
+{
+    __shared__ bf16_t tile[64][64 + 2];
+    const bf16_t* W = blockIdx.z == 0 ? Wq : (blockIdx.z == 1 ? Wk : Wv);
+    bf16_t* dst = Wt + (size_t)blockIdx.z * HD * D;
+    const int c0 = blockIdx.x * 64, r0 = blockIdx.y * 64;
+    const int tx = threadIdx.x & 63, ty = threadIdx.x >> 6;
+    for (int r = ty; r < 64; r += 4) {
+        const int gr = r0 + r;
+        tile[r][tx] = gr < D ? W[(size_t)gr * HD + c0 + tx] : (bf16_t)0;
+    }
+    __syncthreads();
+    for (int c = ty; c < 64; c += 4) {
+        const int gk = r0 + tx;
+        if (gk < D) dst[(size_t)(c0 + c) * D + gk] = tile[tx][c];
+    }
+}
+
+// ---------------------------------------------------------------------------
+// C = A . B^T with both operands k-contiguous.  Square BT x BT tile per
+// workgroup, 2 x 2 wavefronts, 32x32x16 MFMA blocks, 64-deep k slices double
+// buffered in LDS.  The "x side" rows are vectors (with the per-batch row pitch
+// Npad; rows past n read the last real row and are not stored), the "w side"
+// rows are output columns of [q | k | v].
+// For q and k tiles the w side is the A operand, so a lane ends up with four
+// consecutive output columns of one vector (8-byte store into [..][d]); for v
+// tiles the x side is the A operand, so a lane holds four consecutive vectors of
+// one column (8-byte store into the transposed layout).
+// ---------------------------------------------------------------------------
+constexpr int BK = 64;
+constexpr int ROWB = BK * 2 + 16;  // LDS bytes per tile row (padded)
+
+template <int BT>
+__global__ __launch_bounds__(256) void proj_mfma_kernel(int Bsz, int N, int Npad, int D, int H, int d,
+                                                        const bf16_t* __restrict__ X,
+                                                        const bf16_t* __restrict__ Wt, bf16_t* __restrict__ qo,
+                                                        bf16_t* __restrict__ ko, bf16_t* __restrict__ vto,
+                                                        int tiles_x, int tiles_w)
+{
+    constexpr int WT = BT / 2;          // wavefront tile edge
+    constexpr int NB = WT / 32;         // MFMA blocks per edge
+    constexpr int NCH = BT * 8 / 256;   // 16-byte chunks per thread and side
+    constexpr int SIDE = BT * ROWB;
+    __shared__ __attribute__((aligned(16))) unsigned char lds[2 * 2 * SIDE];
+
+    const int tid = threadIdx.x;
+    const int lane = tid & 63, ln = lane & 31, g = lane >> 5;
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+    const int wr = wave >> 1, wc = wave & 1;
+    const int HD = H * d;
+
+    // XCD-aware order: each XCD gets a contiguous run of tiles, walked with the
+    // x-side tile fastest so that a weight tile stays in that XCD's L2.
+    const int n_tiles = tiles_x * tiles_w;
+    const int per_xcd = gridDim.x >> 3;
+    const int tile_id = (blockIdx.x & 7) * per_xcd + (blockIdx.x >> 3);
+    if (tile_id >= n_tiles) return;
+    const int tw = tile_id / tiles_x, tx_ = tile_id - tw * tiles_x;
+    const int x0 = tx_ * BT;   // first x-side row (padded vector index)
+    const int w0 = tw * BT;    // first stacked output column
+    const bool is_v = w0 >= 2 * HD;
+
+    // per-thread source rows: chunk ch = tid + 256*u -> row ch/8, k-chunk ch%8
+    const int kc = tid & 7;
+    unsigned xoff[NCH], woff[NCH];
+#pragma unroll
+    for (int u = 0; u < NCH; ++u) {
+        const int row = (tid >> 3) + 32 * u;
+        const int xr = x0 + row;
+        const int bb = xr / Npad;
+        int i = xr - bb * Npad;
+        i = i < N ? i : N - 1;
+        xoff[u] = (unsigned)(bb * N + i) * (unsigned)D;
+        woff[u] = (unsigned)(w0 + row) * (unsigned)D;
+    }
+
+    f32x16 acc[NB][NB];
+#pragma unroll
+    for (int a = 0; a < NB; ++a)
+#pragma unroll
+        for (int b = 0; b < NB; ++b)
+#pragma unroll
+            for (int r = 0; r < 16; ++r) acc[a][b][r] = 0.f;
+
+    u32x4 xreg[NCH], wreg[NCH];
+    auto issue_loads = [&](int k0) {
+        const int kk = k0 + kc * 8;
+        const bool in = kk < D;  // D is a multiple of 8
+#pragma unroll
+        for (int u = 0; u < NCH; ++u) {
+            u32x4 z = {0u, 0u, 0u, 0u};
+            xreg[u] = in ? *(const u32x4*)(X + (size_t)xoff[u] + kk) : z;
+            wreg[u] = in ? *(const u32x4*)(Wt + (size_t)woff[u] + kk) : z;
+        }
+    };
+    // A operand side first, then B operand side
+    auto stage_store = [&](int buf) {
+        unsigned char* base = lds + buf * 2 * SIDE;
+        unsigned char* xs = base + (is_v ? 0 : SIDE);
+        unsigned char* ws = base + (is_v ? SIDE : 0);
+#pragma unroll
+        for (int u = 0; u < NCH; ++u) {
+            const int row = (tid >> 3) + 32 * u;
+            *(u32x4*)(xs + row * ROWB + kc * 16) = xreg[u];
+            *(u32x4*)(ws + row * ROWB + kc * 16) = wreg[u];
+        }
+    };
+
+    const int nk = (D + BK - 1) / BK;
+    issue_loads(0);
+    stage_store(0);
+    __syncthreads();
+    for (int it = 0; it < nk; ++it) {
+        if (it + 1 < nk) issue_loads((it + 1) * BK);
+        const unsigned char* as = lds + (it & 1) * 2 * SIDE + (wr * WT + ln) * ROWB + g * 16;
+        const unsigned char* bs = lds + (it & 1) * 2 * SIDE + SIDE + (wc * WT + ln) * ROWB + g * 16;
+#pragma unroll
+        for (int ks = 0; ks < BK / 16; ++ks) {
+            u32x4 af[NB], bf[NB];
+#pragma unroll
+            for (int a = 0; a < NB; ++a) af[a] = *(const u32x4*)(as + a * 32 * ROWB + ks * 32);
+#pragma unroll
+            for (int b = 0; b < NB; ++b) bf[b] = *(const u32x4*)(bs + b * 32 * ROWB + ks * 32);
+#pragma unroll
+            for (int a = 0; a < NB; ++a)
+#pragma unroll
+                for (int b = 0; b < NB; ++b) acc[a][b] = mfma32(af[a], bf[b], acc[a][b]);
+        }
+        if (it + 1 < nk) stage_store((it + 1) & 1);
+        __syncthreads();
+    }
+
+    // Epilogue.  acc[a][b][r]: A-side row wr*WT + 32a + acc_row(r,g), B-side row wc*WT + 32b + ln.
+    if (!is_v) {
+        // A side = output columns (4 consecutive per register quad), B side = vectors.
+#pragma unroll
+        for (int b = 0; b < NB; ++b) {
+            const int xr = x0 + wc * WT + 32 * b + ln;
+            const int bb = xr / Npad;
+            const int i = xr - bb * Npad;
+            if (i >= N) continue;
+#pragma unroll
+            for (int a = 0; a < NB; ++a)
+#pragma unroll
+                for (int r4 = 0; r4 < 4; ++r4) {
+                    const int col = w0 + wr * WT + 32 * a + 8 * r4 + 4 * g;  // stacked column of register 4*r4
+                    const int which = col >= HD ? 1 : 0;
+                    const int cc = col - which * HD;
+                    const int h = cc / d, l = cc - h * d;
+                    bf16_t* dst = (which ? ko : qo) + (((size_t)bb * H + h) * Npad + i) * d + l;
+                    u32x2 w;
+                    w[0] = pack_bf16(acc[a][b][4 * r4 + 0], acc[a][b][4 * r4 + 1]);
+                    w[1] = pack_bf16(acc[a][b][4 * r4 + 2], acc[a][b][4 * r4 + 3]);
+                    *(u32x2*)dst = w;
+                }
+        }
+    } else {
+        // A side = vectors (4 consecutive per register quad), B side = output columns of v.
+#pragma unroll
+        for (int b = 0; b < NB; ++b) {
+            const int cc = w0 - 2 * HD + wc * WT + 32 * b + ln;
+            const int h = cc / d, l = cc - h * d;
+#pragma unroll
+            for (int a = 0; a < NB; ++a)
+#pragma unroll
+                for (int r4 = 0; r4 < 4; ++r4) {
+                    const int xr = x0 + wr * WT + 32 * a + 8 * r4 + 4 * g;  // vector of register 4*r4
+                    const int bb = xr / Npad;
+                    const int i = xr - bb * Npad;
+                    if (i >= N) continue;
+                    const int blk = i >> 6, r64 = i & 63;
+                    const int slot = (r64 & 48) | vt_slot16(r64 & 15);
+                    bf16_t* dst = vto + ((((size_t)bb * H + h) * (Npad >> 6) + blk) * d + l) * 64 + slot;
+                    u32x2 w;
+                    w[0] = pack_bf16(acc[a][b][4 * r4 + 0], acc[a][b][4 * r4 + 1]);
+                    w[1] = pack_bf16(acc[a][b][4 * r4 + 2], acc[a][b][4 * r4 + 3]);
+                    *(u32x2*)dst = w;
+                }
+        }
+    }
+}
+
+template <int BT>
+hipError_t launch_bt(const Problem& pb, const bf16_t* X, const bf16_t* Wt, bf16_t* q, bf16_t* k, bf16_t* vt,
+                     hipStream_t s)
+{
+    const int tiles_x = pb.B * pb.Npad / BT;
+    const int tiles_w = 3 * pb.H * pb.d / BT;
+    const int grid = ((tiles_x * tiles_w + 7) / 8) * 8;
+    hipLaunchKernelGGL(proj_mfma_kernel<BT>, dim3(grid), dim3(256), 0, s, pb.B, pb.N, pb.Npad, pb.D, pb.H, pb.d, X, Wt,
+                       q, k, vt, tiles_x, tiles_w);
+    return hipGetLastError();
+}
+
+}  // namespace
+
+hipError_t launch_transpose_w(const Problem& pb, const bf16_t* Wq, const bf16_t* Wk, const bf16_t* Wv, bf16_t* Wt,
+                              hipStream_t s)
+{
+    const int HD = pb.H * pb.d;
+    hipLaunchKernelGGL(transpose_w_kernel, dim3(HD / 64, (pb.D + 63) / 64, 3), dim3(256), 0, s, pb.D, HD, Wq, Wk, Wv,
+                       Wt);
+    return hipGetLastError();
+}
+
+hipError_t launch_proj_mfma(const Problem& pb, const bf16_t* X, const bf16_t* Wt, bf16_t* q, bf16_t* k, bf16_t* vt,
+                            hipStream_t s)
+{
+    // Largest square tile that divides the per-matrix column count (so a tile never
+    // mixes q, k and v columns) and still gives every CU a few tiles.
+    const int HD = pb.H * pb.d;
+    const long rows = (long)pb.B * pb.Npad;
+    if (HD % 256 == 0 && rows % 256 == 0 && (rows / 256) * (3L * HD / 256) >= 512)
+        return launch_bt<256>(pb, X, Wt, q, k, vt, s);
+    if (HD % 128 == 0) return launch_bt<128>(pb, X, Wt, q, k, vt, s);
+    return launch_bt<64>(pb, X, Wt, q, k, vt, s);
+}
+
+}  // namespace attnring

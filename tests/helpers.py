@@ -1,0 +1,86 @@
+"""Shared plumbing of the GPU parity tests: run the library through its C ABI
+binding on seeded inputs and fetch what the CPU checker says for the same inputs."""
+import math
+
+import numpy as np
+
+from oracle import attn_oracle as orc
+from paper_2012_01114_amd import attnring as ar
+from paper_2012_01114_amd import inputs
+
+
+def tol_check(got, ref, dtype):
+    """Parity bar.  f32: |g-r| <= 1e-5*|r| + 1e-5*max|r|.  bf16: |g-r| <= 2e-2."""
+    got = np.asarray(got, dtype=np.float64)
+    ref = np.asarray(ref, dtype=np.float64)
+    assert got.shape == ref.shape
+    assert np.all(np.isfinite(got)), "non-finite output"
+    err = np.abs(got - ref)
+    if dtype == "f32":
+        bound = 1e-5 * np.abs(ref) + 1e-5 * np.max(np.abs(ref))
+    else:
+        bound = np.full_like(ref, 2e-2)
+    bad = err > bound
+    assert not bad.any(), (f"{int(bad.sum())} of {bad.size} elements out of tolerance; "
+                           f"max err {err.max():.3e} at {np.unravel_index(err.argmax(), err.shape)}")
+    return float(err.max())
+
+
+def default_scale(w, scale):
+    return (1.0 / math.sqrt(w.d_k)) if scale == 0.0 else scale
+
+
+class GpuRun:
+    """One context + device copies of one workload's inputs."""
+
+    def __init__(self, w, stored, scale=0.0, flags=0):
+        import torch
+        self.torch = torch
+        self.w = w
+        dev = torch.device("cuda:0")
+        self.dt = ar.ATTN_F32 if w.dtype == "f32" else ar.ATTN_BF16
+        self.X = stored["X"].to(dev)
+        self.W = [None if stored[k] is None else stored[k].to(dev) for k in ("Wq", "Wk", "Wv")]
+        self.lens = None
+        if stored.get("lens") is not None:
+            self.lens = torch.from_numpy(np.asarray(stored["lens"], dtype=np.int32)).to(dev)
+        self.ctx = ar.attn_init(w.batch, w.n, w.d_model, w.n_heads, w.d_k, w.p, self.dt, scale, flags)
+        ar.attn_set_key_lengths(self.ctx, self.lens)
+        self.out = torch.full((w.batch, w.n, w.hd), float("nan"), dtype=self.X.dtype, device=dev)
+
+    def forward(self, scheme):
+        ar.attn_forward(self.ctx, self.X, self.W[0], self.W[1], self.W[2], scheme, self.out)
+        stats = ar.attn_stats(self.ctx)          # waits for the stream
+        return self.out.to("cpu").to(self.torch.float64).numpy(), stats
+
+    def close(self):
+        if self.ctx is not None:
+            self.torch.cuda.synchronize()
+            ar.attn_destroy(self.ctx)
+            self.ctx = None
+
+
+def oracle_forward(w, f64, scheme, scale, lens=None, **kw):
+    return orc.forward(f64["X"], f64["Wq"], f64["Wk"], f64["Wv"], n_heads=w.n_heads, d_k=w.d_k, p=w.p,
+                       scheme=scheme, scale=default_scale(w, scale), lens=lens, **kw)
+
+
+def oracle_counts(w, scheme, lens=None):
+    return orc.counts(batch=w.batch, n=w.n, n_heads=w.n_heads, p=w.p, scheme=scheme, lens=lens)
+
+
+def check_counts(stats, ref, noskip=False):
+    """Bit-exact comparison of the library's counts with the checker's."""
+    assert stats["pairs_full"] == ref["pairs_full"]
+    assert stats["pairs_needed"] == ref["pairs_needed"]
+    assert stats["pairs_scheduled"] == ref["pairs_scheduled"]
+    assert stats["tiles_full"] == ref["tiles_full"]
+    if noskip:
+        assert stats["tiles_executed"] == ref["tiles_full"]
+    else:
+        assert stats["tiles_executed"] == ref["tiles_executed"]
+        assert stats["pairs_executed"] == ref["pairs_executed"]
+
+
+def custom_workload(name, B, n, D, H, d, p, dtype, scheme, seed, padded=False, len_lo=0, len_hi=0):
+    return inputs.Workload(name, B, n, D, H, d, p, dtype, scheme, seed, padded, len_lo, len_hi)

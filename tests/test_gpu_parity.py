@@ -1,0 +1,203 @@
+"""GPU parity: the HIP library, called through its C ABI, against the float64 CPU
+checker on the same seeded inputs.  Bars: f32 |g-r| <= 1e-5|r| + 1e-5 max|r|;
+bf16 |g-r| <= 2e-2; every count bit-exact."""
+import numpy as np
+import pytest
+
+from oracle import attn_oracle as orc
+from paper_2012_01114_amd import attnring as ar
+from paper_2012_01114_amd import inputs
+from tests import helpers as hp
+
+pytestmark = pytest.mark.gpu
+
+FULL, SYM, CAUSAL = inputs.SCHEME_FULL, inputs.SCHEME_SYMMETRIC, inputs.SCHEME_CAUSAL
+
+
+def _run_and_compare(w, scheme, scale=0.0, lens=None, zero_wq=False, sym_no_proj=False):
+    print(f"[case] {w.name} B{w.batch} N{w.n} D{w.d_model} H{w.n_heads} d{w.d_k} P{w.p} {w.dtype} "
+          f"scheme={scheme} scale={scale} lens={'yes' if lens is not None else 'no'}", flush=True)
+    stored, f64 = inputs.make_inputs(w, zero_wq=zero_wq)
+    stored["lens"] = lens
+    if sym_no_proj:
+        stored["Wq"] = f64["Wq"] = None
+    if scheme == SYM:
+        stored["Wk"] = stored["Wv"] = None
+    run = hp.GpuRun(w, stored, scale=scale)
+    try:
+        got, stats = run.forward(scheme)
+    finally:
+        run.close()
+    ref = hp.oracle_forward(w, f64, scheme, scale, lens=lens)
+    err = hp.tol_check(got, ref, w.dtype)
+    hp.check_counts(stats, hp.oracle_counts(w, scheme, lens))
+    return err, stats
+
+
+# ---- workload 1: Tiny, f32, all three schemes, both scales ---------------------------------
+@pytest.mark.parametrize("scheme", [FULL, SYM, CAUSAL])
+@pytest.mark.parametrize("scale", [0.0, 1.0])
+def test_tiny(scheme, scale):
+    w = inputs.with_scheme(inputs.WORKLOADS["tiny"], scheme)
+    _, stats = _run_and_compare(w, scheme, scale)
+    expect = {FULL: (16, 256), SYM: (12, 192), CAUSAL: (10, 160)}[scheme]
+    assert (stats["tiles_executed"], stats["pairs_executed"]) == expect
+    assert stats["proj_gemms"] == (1 if scheme == SYM else 3)
+
+
+# ---- float path on ragged shapes (several partitions, odd sizes, padding) --------------------
+@pytest.mark.parametrize("shape", [
+    # B, n, D, H, d, p
+    (2, 50, 24, 3, 20, 10),
+    (1, 63, 17, 2, 33, 9),
+    (3, 96, 40, 1, 130, 3),     # d_k > 128, rows per partition > one wavefront pass
+    (1, 7, 5, 1, 3, 7),
+])
+@pytest.mark.parametrize("scheme", [FULL, SYM, CAUSAL])
+@pytest.mark.parametrize("dtype", ["f32", "bf16"])
+def test_float_path_ragged(shape, scheme, dtype):
+    B, n, D, H, d, p = shape
+    w = hp.custom_workload("ragged", B, n, D, H, d, p, dtype, scheme, 4242 + n)
+    _run_and_compare(w, scheme, 0.0)
+    if scheme != SYM:
+        lens = np.random.default_rng(n).integers(0, n + 1, B).astype(np.int32)
+        lens[0] = max(1, n // 3)
+        _run_and_compare(w, scheme, 0.3, lens=lens)
+
+
+def test_symmetric_without_projection():
+    w = hp.custom_workload("symx", 2, 20, 24, 2, 12, 5, "f32", SYM, 77)
+    _, stats = _run_and_compare(w, SYM, 0.2, sym_no_proj=True)
+    assert stats["proj_gemms"] == 0
+
+
+# ---- bf16 MFMA path on small shapes: several tiles and a ragged tail -----------------------------
+@pytest.mark.parametrize("shape", [
+    (2, 320, 64, 2, 64, 40),      # 2.5 row tiles
+    (1, 200, 96, 3, 64, 25),      # n not a multiple of 8
+    (2, 384, 128, 2, 128, 12),    # d_k = 128, partitions of 32 rows
+    (1, 136, 72, 1, 128, 17),     # d_model not a multiple of 64 (k tail)
+    (1, 520, 64, 2, 64, 5),       # partitions larger than a score block (104 rows)
+])
+@pytest.mark.parametrize("scheme", [FULL, CAUSAL])
+def test_mfma_path_small(shape, scheme):
+    B, n, D, H, d, p = shape
+    w = hp.custom_workload("mfma_small", B, n, D, H, d, p, "bf16", scheme, 999 + n)
+    _, stats = _run_and_compare(w, scheme, 0.0)
+    assert (stats["phys_br"], stats["phys_bc"]) == (32, 32)
+    lens = np.random.default_rng(n + 1).integers(1, n + 1, B).astype(np.int32)
+    lens[-1] = n // 2 + 3
+    _run_and_compare(w, scheme, 0.0, lens=lens)
+    _run_and_compare(w, scheme, 0.0, lens=np.zeros(B, dtype=np.int32))
+
+
+# ---- the -inf practice (Sec. 5.1) against skipping: identical bits ------------------------------
+@pytest.mark.parametrize("case", [
+    ("f32", 1, 48, 32, 2, 16, 6),
+    ("bf16", 2, 320, 64, 2, 64, 40),
+    ("bf16", 1, 264, 64, 1, 128, 33),
+])
+@pytest.mark.parametrize("scheme", [FULL, SYM, CAUSAL])
+def test_skip_equals_noskip_bits(case, scheme):
+    dtype, B, n, D, H, d, p = case
+    w = hp.custom_workload("bits", B, n, D, H, d, p, dtype, scheme, 31 + n)
+    stored, _ = inputs.make_inputs(w)
+    lens = None
+    if scheme != SYM:
+        lens = np.random.default_rng(5).integers(1, n + 1, B).astype(np.int32)
+    stored["lens"] = lens
+    outs = []
+    for flags in (0, ar.ATTN_FLAG_NO_SKIP):
+        run = hp.GpuRun(w, stored, flags=flags)
+        try:
+            got, stats = run.forward(scheme)
+        finally:
+            run.close()
+        outs.append(got)
+        hp.check_counts(stats, hp.oracle_counts(w, scheme, lens), noskip=bool(flags))
+    assert np.array_equal(outs[0], outs[1])
+
+
+# ---- workloads 2 and 3 in full -------------------------------------------------------------------
+@pytest.mark.parametrize("name", ["encoder", "causal"])
+def test_encoder_and_causal_full(name):
+    w = inputs.WORKLOADS[name]
+    err, stats = _run_and_compare(w, w.scheme, 0.0)
+    print(f"{name}: max abs err {err:.3e}; tiles {stats['tiles_executed']}/{stats['tiles_full']}")
+    if name == "causal":
+        assert stats["pairs_needed"][0] == 50380800
+        assert stats["tiles_executed"] == 96 * 8256
+
+
+def test_repeat_calls_are_stable():
+    """Back-to-back calls on one context give identical bits and identical counts."""
+    w = inputs.WORKLOADS["causal"]
+    stored, _ = inputs.make_inputs(w)
+    run = hp.GpuRun(w, stored)
+    try:
+        a, sa = run.forward(w.scheme)
+        b, sb = run.forward(w.scheme)
+    finally:
+        run.close()
+    assert np.array_equal(a, b) and sa == sb
+
+
+# ---- workloads 4 and 5: sampled rows + counts + a property that holds at any size --------------
+def _sampled_rows(w, lens, picks):
+    stored, f64 = inputs.make_inputs(w)
+    stored["lens"] = lens
+    run = hp.GpuRun(w, stored)
+    try:
+        got, stats = run.forward(w.scheme)
+    finally:
+        run.close()
+    assert np.all(np.isfinite(got))
+    worst = 0.0
+    for (b, h, rows) in picks:
+        print(f"[rows] b={b} h={h} rows={rows}", flush=True)
+        ref = orc.head_rows(f64["X"], f64["Wq"], f64["Wk"], f64["Wv"], n_heads=w.n_heads, d_k=w.d_k, p=w.p,
+                            scheme=w.scheme, scale=hp.default_scale(w, 0.0), b=b, h=h, rows=rows, lens=lens)
+        worst = max(worst, hp.tol_check(got[b, rows, h * w.d_k:(h + 1) * w.d_k], ref, w.dtype))
+    hp.check_counts(stats, hp.oracle_counts(w, w.scheme, lens))
+    return worst, stats
+
+
+def test_long_causal_sampled():
+    w = inputs.WORKLOADS["long"]
+    picks = [(0, 0, [0, 1, 31, 32, 127, 128, 129, 4095, 4096, 8191]),
+             (0, 17, [63, 64, 2047, 6000, 8190]),
+             (0, 31, [5, 1000, 4097, 8064, 8191])]
+    worst, stats = _sampled_rows(w, None, picks)
+    print(f"long: max abs err on samples {worst:.3e}")
+    assert stats["pairs_needed"][0] == 1073872896
+    assert stats["tiles_executed"] == 32 * 32896
+
+
+def test_padded_batch_sampled():
+    w = inputs.WORKLOADS["padded"]
+    lens = inputs.draw_lengths(w)
+    b_short, b_long = int(np.argmin(lens)), int(np.argmax(lens))
+    L0, L1 = int(lens[b_short]), int(lens[b_long])
+    picks = [(b_short, 0, [0, L0 - 1, L0, L0 + 1, 2047]),
+             (b_long, 15, [0, 64, L1 - 1, min(L1, 2047), 2047]),
+             (7, 9, [1, 500, int(lens[7]) - 1, 2040])]
+    worst, stats = _sampled_rows(w, lens, picks)
+    print(f"padded: max abs err on samples {worst:.3e}")
+    closed = sum(int(L) * (int(L) + 1) // 2 + (w.n - int(L)) * int(L) for L in lens) * w.n_heads
+    assert stats["pairs_needed"][0] == closed
+
+
+def test_zero_query_weights_give_prefix_means_at_full_size():
+    """Wq = 0 makes all allowed weights equal, so y_i is the mean of v_0..v_i: checked for
+    every row of sampled heads of the long workload against numpy's float64 matmul."""
+    w = inputs.WORKLOADS["long"]
+    stored, f64 = inputs.make_inputs(w, zero_wq=True)
+    run = hp.GpuRun(w, stored)
+    try:
+        got, _ = run.forward(w.scheme)
+    finally:
+        run.close()
+    for h in (0, 13, 31):
+        V = f64["X"][0] @ f64["Wv"][:, h * w.d_k:(h + 1) * w.d_k]
+        ref = np.cumsum(V, 0) / np.arange(1, w.n + 1)[:, None]
+        hp.tol_check(got[0, :, h * w.d_k:(h + 1) * w.d_k], ref, w.dtype)
