@@ -10,12 +10,15 @@
 // Masked scheme: workgroup x handles row tiles T-1-x and x, the packing of row
 // n-i with row i that equalises the work per PE (Sec. 5.2).
 //
-// Data path per key block: K[64][d] and V^T[d][64] are staged through LDS
-// (double buffered, one barrier per block).  Scores are computed transposed,
-// S^T = K.Q^T, so that a lane holds 16 keys of ONE query per 32x32 block: the
-// row maximum and row sum of the online softmax need one cross-lane exchange,
-// and the exponentials, converted to bf16, are already in B-operand layout for
-// O^T += V^T.P^T.
+// Data path per key block: K[64][d] and V^T[d][64] go from global memory
+// straight into LDS (global_load_lds, 16 bytes per lane), double buffered, one
+// barrier per block.  LDS rows are unpadded; the 16-byte chunks of a row are
+// XOR-swizzled with the row index so that the 128-bit operand reads of 16
+// consecutive rows hit 16 different bank groups.  Scores are computed
+// transposed, S^T = K.Q^T, so that a lane holds 16 keys of ONE query per 32x32
+// block: the row maximum and row sum of the online softmax need one cross-lane
+// exchange, and the exponentials, converted to bf16, are already in B-operand
+// layout for O^T += V^T.P^T.
 #include "mfma_common.h"
 
 namespace attnring {
@@ -24,15 +27,6 @@ namespace {
 constexpr int BR = 128;  // query rows per workgroup tile
 constexpr int BC = 64;   // keys per staged block
 constexpr int NTHREADS = 256;
-
-template <int DK>
-struct Lds {
-    static constexpr int KS = DK * 2 + 16;  // bytes per key row (padded: conflict-free b128 reads)
-    static constexpr int VS = BC * 2 + 16;  // bytes per V^T row
-    static constexpr int K_BYTES = BC * KS;
-    static constexpr int V_BYTES = DK * VS;
-    static constexpr int STAGE = K_BYTES + V_BYTES;
-};
 
 struct CountCfg {
     int b;        // rows per logical PE
@@ -45,6 +39,128 @@ __device__ __forceinline__ unsigned cdiv_b(unsigned x, const CountCfg& cc)
     const unsigned y = x + (unsigned)cc.b - 1u;
     return cc.b_shift >= 0 ? (y >> cc.b_shift) : y / (unsigned)cc.b;
 }
+__device__ __forceinline__ bool is_multiple(int x, const CountCfg& cc)
+{
+    return cc.b_shift >= 0 ? (x & (cc.b - 1)) == 0 : (x % cc.b) == 0;
+}
+
+// Swizzled chunk position inside an LDS row of ROWB bytes (256 or 128).
+template <int ROWB>
+__device__ __forceinline__ int swz(int chunk, int row)
+{
+    return ROWB == 256 ? (chunk ^ (row & 15)) : (chunk ^ ((row >> 1) & 7));
+}
+
+// One wavefront copies 1 KiB pieces of a [rows][ROWB] tile from global memory to
+// LDS: piece m holds rows m*RPP .. ; lane L lands at byte 16*L of the piece and
+// fetches the chunk that belongs there under the swizzle.
+template <int ROWB>
+__device__ __forceinline__ void dma_pieces(const unsigned char* __restrict__ gsrc, unsigned char* ldst, int first,
+                                           int count, int step, int lane)
+{
+    constexpr int CPR = ROWB / 16;  // chunks per row
+    constexpr int RPP = 64 / CPR;   // rows per piece
+    const int rl = lane / CPR, p = lane % CPR;
+#pragma unroll
+    for (int u = 0; u < count; ++u) {
+        const int m = first + u * step;
+        const int row = m * RPP + rl;
+        const int c = swz<ROWB>(p, row);
+        __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void*)(gsrc + row * ROWB + c * 16),
+                                         (__attribute__((address_space(3))) void*)(ldst + m * 1024), 16, 0, 0);
+    }
+}
+
+template <int DK, bool CAUSAL>
+struct Tile {
+    static constexpr int NKS = DK / 16;         // k-steps of the score product
+    static constexpr int NDB = DK / 32;         // 32-row blocks of O^T
+    static constexpr int KROWB = DK * 2;        // bytes per key row in LDS
+    static constexpr int K_BYTES = BC * KROWB;  // 8 or 16 KiB
+    static constexpr int V_BYTES = DK * BC * 2; // same size
+    static constexpr int STAGE = K_BYTES + V_BYTES;
+
+    // Everything one wavefront carries along a row tile.
+    struct State {
+        f32x16 O[NDB];
+        float m_run, l_run;
+    };
+
+    // One 32-key score block of the staged tile, all three phases.
+    // MASK = false: every pair of the 32 x 32 block is allowed (no test at all).
+    // MASK = true : pairs are tested one by one (diagonal, key length, debug mode).
+    // The running maximum is only raised when a row's scores exceed it by more than
+    // 2^RAISE; until then exponentials may reach 2^RAISE, which fp32 sums and bf16
+    // operands hold without loss, and the 16*NDB accumulator rescales are skipped.
+    static constexpr float RAISE = 8.f;
+    template <bool MASK>
+    static __device__ __forceinline__ void block(State& st, const u32x4 (&qf)[NKS], const unsigned char* kl,
+                                                 const int (&koff)[NKS], const int (&voff)[4], int jb, float c2,
+                                                 int kb, int i, int g, int len)
+    {
+        // operand reads of phase 1: all K fragments of the block at once
+        u32x4 kf[NKS], vf[2][NDB];
+#pragma unroll
+        for (int ks = 0; ks < NKS; ++ks) kf[ks] = *(const u32x4*)(kl + koff[ks] + jb * 32 * KROWB);
+        __builtin_amdgcn_sched_barrier(0);
+        // phase 1 (Eq. (1)): S^T[key][query] = sum_l k[key][l] q[query][l]
+        f32x16 S;
+#pragma unroll
+        for (int r = 0; r < 16; ++r) S[r] = 0.f;
+#pragma unroll
+        for (int ks = 0; ks < NKS; ++ks) S = mfma32(kf[ks], qf[ks], S);
+        __builtin_amdgcn_sched_barrier(0);
+        // operand reads of phase 3, issued now so that they land during the softmax
+#pragma unroll
+        for (int hf = 0; hf < 2; ++hf)
+#pragma unroll
+            for (int db = 0; db < NDB; ++db)
+                vf[hf][db] = *(const u32x4*)(kl + voff[2 * jb + hf] + db * 32 * (BC * 2));
+        __builtin_amdgcn_sched_barrier(0);
+        if (MASK) {
+#pragma unroll
+            for (int r = 0; r < 16; ++r) {
+                const int j = kb + acc_row(r, g);
+                const bool ok = j < len && (!CAUSAL || j <= i);
+                S[r] = ok ? S[r] : -INFINITY;
+            }
+        }
+        // phase 2 (Eq. (2)), online: running maximum and sum per query row
+        float mx = S[0];
+#pragma unroll
+        for (int r = 1; r < 16; ++r) mx = fmaxf(mx, S[r]);
+        mx = fmaxf(mx, __shfl_xor(mx, 32, 64)) * c2;
+        const bool moved = mx > st.m_run + RAISE;
+        const float m_new = moved ? mx : st.m_run;
+        const float m_use = (MASK && m_new == -INFINITY) ? 0.f : m_new;
+        const float alpha = __builtin_amdgcn_exp2f(st.m_run - m_use);
+        st.m_run = m_new;
+        float psum = 0.f;
+        u32x4 pf[2];
+#pragma unroll
+        for (int hf = 0; hf < 2; ++hf)
+#pragma unroll
+            for (int w = 0; w < 4; ++w) {
+                const float p0 = __builtin_amdgcn_exp2f(__builtin_fmaf(S[8 * hf + 2 * w], c2, -m_use));
+                const float p1 = __builtin_amdgcn_exp2f(__builtin_fmaf(S[8 * hf + 2 * w + 1], c2, -m_use));
+                psum += p0 + p1;
+                pf[hf][w] = pack_bf16(p0, p1);
+            }
+        st.l_run = st.l_run * alpha + psum;
+        if (__builtin_amdgcn_ballot_w64(moved) != 0ull) {
+#pragma unroll
+            for (int db = 0; db < NDB; ++db)
+#pragma unroll
+                for (int r = 0; r < 16; ++r) st.O[db][r] *= alpha;
+        }
+        __builtin_amdgcn_sched_barrier(0);
+        // phase 3 (Eq. (3)): O^T[col][query] += sum_key V^T[col][key] P^T[key][query]
+#pragma unroll
+        for (int hf = 0; hf < 2; ++hf)
+#pragma unroll
+            for (int db = 0; db < NDB; ++db) st.O[db] = mfma32(vf[hf][db], pf[hf], st.O[db]);
+    }
+};
 
 template <int DK, bool CAUSAL>
 __global__ __launch_bounds__(NTHREADS, 2) void attn_mfma_kernel(Problem pb, CountCfg cc, const bf16_t* __restrict__ q,
@@ -53,12 +169,11 @@ __global__ __launch_bounds__(NTHREADS, 2) void attn_mfma_kernel(Problem pb, Coun
                                                                 bf16_t* __restrict__ out, int n_qtiles, int per_head,
                                                                 int n_work)
 {
-    typedef Lds<DK> L;
-    constexpr int NKS = DK / 16;  // k-steps of the score product
-    constexpr int NDB = DK / 32;  // 32-row blocks of O^T
-    constexpr int KCH = BC * DK * 2 / 16 / NTHREADS;  // 16-byte chunks per thread, K block
-    constexpr int VCH = KCH;                          // V^T block has the same size
-    __shared__ __attribute__((aligned(16))) unsigned char lds[2 * L::STAGE];
+    typedef Tile<DK, CAUSAL> T;
+    constexpr int NKS = T::NKS, NDB = T::NDB;
+    constexpr int KPIECES = T::K_BYTES / 1024 / 4;  // 1 KiB pieces per wavefront
+    constexpr int VPIECES = T::V_BYTES / 1024 / 4;
+    __shared__ __attribute__((aligned(1024))) unsigned char lds[2 * T::STAGE];
 
     const int tid = threadIdx.x;
     const int lane = tid & 63, ln = lane & 31, g = lane >> 5;
@@ -83,10 +198,20 @@ __global__ __launch_bounds__(NTHREADS, 2) void attn_mfma_kernel(Problem pb, Coun
     const unsigned char* kh = (const unsigned char*)(k + (size_t)bh * Npad * DK);
     const unsigned char* vh = (const unsigned char*)(vt + (size_t)bh * Npad * DK);
 
-    unsigned cnt_logical = 0;  // per lane
-    unsigned cnt_phys = 0;     // per wave (lane 0 adds)
+    // Swizzled LDS byte offsets of this lane's operand reads within a stage (the second
+    // 32-key block of a tile lies 32 key rows higher).
+    int koff[NKS], voff[4];
+#pragma unroll
+    for (int ks = 0; ks < NKS; ++ks) koff[ks] = ln * T::KROWB + swz<T::KROWB>(2 * ks + g, ln) * 16;
+#pragma unroll
+    for (int ch = 0; ch < 4; ++ch) voff[ch] = T::K_BYTES + ln * (BC * 2) + swz<BC * 2>(2 * ch + g, ln) * 16;
+
+    unsigned cnt_edge = 0;      // logical tiles found lane by lane in edge blocks
+    unsigned cnt_interior = 0;  // logical tiles of fully allowed blocks (wave-uniform)
+    unsigned cnt_phys = 0;      // 32 x 32 score blocks issued (wave-uniform)
 
     const int n_pass = CAUSAL ? 2 : 1;
+#pragma nounroll
     for (int pass = 0; pass < n_pass; ++pass) {
         int I;
         if (CAUSAL) {
@@ -99,172 +224,130 @@ __global__ __launch_bounds__(NTHREADS, 2) void attn_mfma_kernel(Problem pb, Coun
         const int i = i0w + ln;              // this lane's query row
         const bool wave_active = i0w < N;
 
-        // Key blocks that hold a needed pair: J = 0 .. nJ-1.
+        // The walk over key blocks.  Needed blocks are J = 0 .. nJ-1.
+        //   masked scheme: J = Js, Js-1, .., 0 (own diagonal block first);
+        //   FULL: the block cut by the key length first (if any), then the whole
+        //         blocks in ring order from the own block.
+        // In debug mode the blocks with no needed pair are walked first; they change nothing.
         int nJ = (len + BC - 1) / BC;
         if (CAUSAL) nJ = nJ < 2 * I + 2 ? nJ : 2 * I + 2;
-        const int nT = pb.noskip ? nkt_all : nJ;
-        const int modJ = nT;
-        int Js = 2 * I + 1;
-        if (Js > nT - 1) Js = nT - 1;
+        const int n_dead = pb.noskip ? nkt_all - nJ : 0;
+        const int nT = nJ + n_dead;
+        const int has_cut = (!CAUSAL && (len % BC) != 0) ? 1 : 0;
+        const int n_ring = nJ - has_cut;                      // FULL: whole blocks
+        const int Js = CAUSAL ? nJ - 1 : (2 * I + 1 < n_ring ? 2 * I + 1 : n_ring - 1);
+        auto block_of_step = [&](int t) -> int {
+            if (t < n_dead) return nkt_all - 1 - t;
+            t -= n_dead;
+            if (CAUSAL) return Js - t;
+            if (t < has_cut) return nJ - 1;
+            int J = Js - (t - has_cut);
+            return J < 0 ? J + n_ring : J;
+        };
+        // Steps this wavefront takes through the general code; the rest are blocks in
+        // which every pair is allowed.
+        int n_gen;
+        if (pb.noskip || !wave_active) {
+            n_gen = nT;
+        } else if (CAUSAL) {
+            int j_int = (i0w + 1) / BC - 1;                  // last block entirely at or below row i0w
+            const int j_len = len / BC - 1;                  // last block entirely below the key length
+            j_int = j_int < j_len ? j_int : j_len;
+            n_gen = Js - j_int;
+            n_gen = n_gen < 0 ? 0 : (n_gen > nT ? nT : n_gen);
+        } else {
+            n_gen = has_cut;
+        }
 
-        f32x16 O[NDB];
+        typename T::State st;
 #pragma unroll
         for (int db = 0; db < NDB; ++db)
 #pragma unroll
-            for (int r = 0; r < 16; ++r) O[db][r] = 0.f;
-        float m_run = -INFINITY, l_run = 0.f;
+            for (int r = 0; r < 16; ++r) st.O[db][r] = 0.f;
+        st.m_run = -INFINITY;
+        st.l_run = 0.f;
 
         if (nT > 0) {
-            // Q rows of this wavefront as B operand (rows >= N of the workspace are zero).
+            // Q rows of this wavefront as B operand (rows >= n of the workspace are zero).
             u32x4 qf[NKS];
 #pragma unroll
-            for (int ks = 0; ks < NKS; ++ks)
-                qf[ks] = *(const u32x4*)(qh + (size_t)i * DK + ks * 16 + g * 8);
+            for (int ks = 0; ks < NKS; ++ks) qf[ks] = *(const u32x4*)(qh + (size_t)i * DK + ks * 16 + g * 8);
 
-            const bool row_anchor = i < N && (cc.b_shift >= 0 ? (i & (cc.b - 1)) == 0 : (i % cc.b) == 0);
+            const bool row_anchor = i < N && is_multiple(i, cc);
             const unsigned nr_anchor = cdiv_b(min(i0w + 32, N), cc) - cdiv_b(min(i0w, N), cc);
 
-            u32x4 kreg[KCH], vreg[VCH];
-            auto issue_loads = [&](int J) {
-                const unsigned char* ksrc = kh + (size_t)J * (BC * DK * 2);
-                const unsigned char* vsrc = vh + (size_t)J * (BC * DK * 2);
-#pragma unroll
-                for (int u = 0; u < KCH; ++u) kreg[u] = *(const u32x4*)(ksrc + (size_t)(tid + u * NTHREADS) * 16);
-#pragma unroll
-                for (int u = 0; u < VCH; ++u) vreg[u] = *(const u32x4*)(vsrc + (size_t)(tid + u * NTHREADS) * 16);
-            };
-            auto stage_store = [&](int buf) {
-                unsigned char* kd = lds + buf * L::STAGE;
-                unsigned char* vd = kd + L::K_BYTES;
-#pragma unroll
-                for (int u = 0; u < KCH; ++u) {
-                    const int ch = tid + u * NTHREADS;
-                    const int row = ch / (DK / 8), col = ch % (DK / 8);
-                    *(u32x4*)(kd + row * L::KS + col * 16) = kreg[u];
-                }
-#pragma unroll
-                for (int u = 0; u < VCH; ++u) {
-                    const int ch = tid + u * NTHREADS;
-                    const int row = ch / (BC / 8), col = ch % (BC / 8);
-                    *(u32x4*)(vd + row * L::VS + col * 16) = vreg[u];
-                }
+            auto issue_loads = [&](int J, int buf) {
+                unsigned char* base = lds + buf * T::STAGE;
+                dma_pieces<T::KROWB>(kh + (size_t)J * T::K_BYTES, base, wave, KPIECES, 4, lane);
+                dma_pieces<BC * 2>(vh + (size_t)J * T::V_BYTES, base + T::K_BYTES, wave, VPIECES, 4, lane);
             };
 
-            issue_loads(Js);
-            stage_store(0);
+            issue_loads(block_of_step(0), 0);
+            __builtin_amdgcn_s_waitcnt(0x0F70);  // vmcnt(0): the LDS writes of this wavefront have landed
             __syncthreads();
 
-            for (int t = 0; t < nT; ++t) {
-                int J = Js - t;
-                if (J < 0) J += modJ;
-                if (t + 1 < nT) {
-                    int Jn = J - 1;
-                    if (Jn < 0) Jn += modJ;
-                    issue_loads(Jn);
-                }
-                const unsigned char* kl = lds + (t & 1) * L::STAGE;
-                const unsigned char* vl = kl + L::K_BYTES;
-
-                // Which of the two 32-key score blocks this wavefront issues.
-                const int kb0 = J * BC;
-                bool need[2], edge[2];
-#pragma unroll
-                for (int jb = 0; jb < 2; ++jb) {
-                    const int kb = kb0 + 32 * jb;
-                    need[jb] = wave_active && (pb.noskip || (kb < len && (!CAUSAL || kb <= i0w)));
-                    edge[jb] = pb.noskip || kb + 32 > len || (CAUSAL && kb + 31 > i0w);
-                }
-                if (need[0] || need[1]) {
-                    f32x16 S[2];
-#pragma unroll
-                    for (int jb = 0; jb < 2; ++jb)
-#pragma unroll
-                        for (int r = 0; r < 16; ++r) S[jb][r] = 0.f;
-                    // phase 1 (Eq. (1)): S^T[key][query] = sum_l k[key][l] q[query][l]
-#pragma unroll
-                    for (int ks = 0; ks < NKS; ++ks) {
-#pragma unroll
-                        for (int jb = 0; jb < 2; ++jb) {
-                            if (need[jb]) {
-                                const u32x4 kf = *(const u32x4*)(kl + (32 * jb + ln) * L::KS + (2 * ks + g) * 16);
-                                S[jb] = mfma32(kf, qf[ks], S[jb]);
-                            }
-                        }
-                    }
-                    // counting and element mask on blocks that touch the diagonal or the key length
-                    float mx = -INFINITY;
+            // ---- general steps: blocks may be skipped or masked pair by pair ----
+            int t = 0;
+#pragma nounroll
+            for (; t < n_gen; ++t) {
+                const int J = block_of_step(t);
+                if (t + 1 < nT) issue_loads(block_of_step(t + 1), (t + 1) & 1);
+                const unsigned char* kl = lds + (t & 1) * T::STAGE;
+                if (wave_active) {
 #pragma unroll
                     for (int jb = 0; jb < 2; ++jb) {
-                        if (!need[jb]) continue;
-                        const int kb = kb0 + 32 * jb;
-                        cnt_phys += 1;
-                        if (edge[jb] || i0w + 32 > N || kb + 32 > N) {
-#pragma unroll
-                            for (int r = 0; r < 16; ++r) {
-                                const int j = kb + acc_row(r, g);
-                                const bool ok = j < len && (!CAUSAL || j <= i);
-                                if (edge[jb]) S[jb][r] = ok ? S[jb][r] : -INFINITY;
-                                const bool col_anchor = cc.b_shift >= 0 ? (j & (cc.b - 1)) == 0 : (j % cc.b) == 0;
-                                cnt_logical += (row_anchor && col_anchor && j < N && (ok || pb.noskip)) ? 1u : 0u;
-                            }
-                        } else if (lane == 0) {
-                            cnt_logical += nr_anchor * (cdiv_b(kb + 32, cc) - cdiv_b(kb, cc));
-                        }
-#pragma unroll
-                        for (int r = 0; r < 16; ++r) mx = fmaxf(mx, S[jb][r]);
-                    }
-                    // phase 2 (Eq. (2)), online: running maximum and sum per query row
-                    mx = fmaxf(mx, __shfl_xor(mx, 32, 64));
-                    const float m_new = fmaxf(m_run, mx * c2);
-                    const float m_safe = m_new == -INFINITY ? 0.f : m_new;
-                    const float alpha = __builtin_amdgcn_exp2f(m_run - m_safe);
-                    m_run = m_new;
-                    float psum = 0.f;
-                    u32x4 pf[4];
-#pragma unroll
-                    for (int jb = 0; jb < 2; ++jb) {
-                        if (need[jb]) {
-                            float p[16];
-#pragma unroll
-                            for (int r = 0; r < 16; ++r) {
-                                p[r] = __builtin_amdgcn_exp2f(__builtin_fmaf(S[jb][r], c2, -m_safe));
-                                psum += p[r];
-                            }
-#pragma unroll
-                            for (int hf = 0; hf < 2; ++hf)
-#pragma unroll
-                                for (int w = 0; w < 4; ++w)
-                                    pf[2 * jb + hf][w] = pack_bf16(p[8 * hf + 2 * w], p[8 * hf + 2 * w + 1]);
-                        }
-                    }
-                    l_run = l_run * alpha + psum;
-#pragma unroll
-                    for (int db = 0; db < NDB; ++db)
-#pragma unroll
-                        for (int r = 0; r < 16; ++r) O[db][r] *= alpha;
-                    // phase 3 (Eq. (3)): O^T[col][query] += sum_key V^T[col][key] P^T[key][query]
-#pragma unroll
-                    for (int jb = 0; jb < 2; ++jb) {
-                        if (need[jb]) {
-#pragma unroll
-                            for (int hf = 0; hf < 2; ++hf) {
-                                const int ch = 2 * jb + hf;
-#pragma unroll
-                                for (int db = 0; db < NDB; ++db) {
-                                    const u32x4 vf = *(const u32x4*)(vl + (32 * db + ln) * L::VS + (2 * ch + g) * 16);
-                                    O[db] = mfma32(vf, pf[ch], O[db]);
+                        const int kb = J * BC + 32 * jb;
+                        const bool need = pb.noskip || (kb < len && (!CAUSAL || kb <= i0w));
+                        if (need) {  // otherwise: redundant block, never issued
+                            const bool edge = pb.noskip || kb + 32 > len || (CAUSAL && kb + 31 > i0w);
+                            cnt_phys += 1;
+                            if (edge) T::template block<true>(st, qf, kl, koff, voff, jb, c2, kb, i, g, len);
+                            else T::template block<false>(st, qf, kl, koff, voff, jb, c2, kb, i, g, len);
+                            if (edge || i0w + 32 > N) {
+                                // logical tiles whose first pair lies in this block and is allowed:
+                                // each such pair is seen by the lane that holds it in the accumulator
+                                if (row_anchor) {
+                                    const int jend = min(kb + 32, N);
+#pragma nounroll
+                                    for (int j = (int)cdiv_b(kb, cc) * cc.b; j < jend; j += cc.b) {
+                                        const bool mine = (((j - kb) >> 2) & 1) == g;
+                                        const bool ok = j < len && (!CAUSAL || j <= i);
+                                        cnt_edge += (mine && (ok || pb.noskip)) ? 1u : 0u;
+                                    }
                                 }
+                            } else {
+                                cnt_interior += nr_anchor * (cdiv_b(kb + 32, cc) - cdiv_b(kb, cc));
                             }
                         }
                     }
                 }
-                if (t + 1 < nT) stage_store((t + 1) & 1);
+                __builtin_amdgcn_s_waitcnt(0x0F70);  // the next block is in LDS before anyone reads it
+                __syncthreads();
+            }
+            // ---- the rest: every pair allowed; no test, no branch ----
+            if (t < nT) {
+                // These steps cover a contiguous range of whole blocks; count their tiles from the range.
+                const int j_hi = block_of_step(t);
+                const int j_lo = CAUSAL ? 0 : 0;
+                const int n_fast = nT - t;
+                cnt_phys += 2u * (unsigned)n_fast;
+                const int k_hi = CAUSAL ? (j_hi + 1) * BC : n_ring * BC;
+                cnt_interior += nr_anchor * (cdiv_b(k_hi, cc) - cdiv_b(j_lo * BC, cc));
+            }
+#pragma nounroll
+            for (; t < nT; ++t) {
+                const int J = block_of_step(t);
+                if (t + 1 < nT) issue_loads(block_of_step(t + 1), (t + 1) & 1);
+                const unsigned char* kl = lds + (t & 1) * T::STAGE;
+                T::template block<false>(st, qf, kl, koff, voff, 0, c2, J * BC, i, g, len);
+                T::template block<false>(st, qf, kl, koff, voff, 1, c2, J * BC + 32, i, g, len);
+                __builtin_amdgcn_s_waitcnt(0x0F70);
                 __syncthreads();
             }
         }
 
         // y_i = O_i / l_i ; a row with no allowed pair is zero.
-        const float l_tot = l_run + __shfl_xor(l_run, 32, 64);
+        const float l_tot = st.l_run + __shfl_xor(st.l_run, 32, 64);
         if (i < N) {
             const float inv = l_tot > 0.f ? 1.f / l_tot : 0.f;
             bf16_t* orow = out + ((size_t)bb * N + i) * ((size_t)pb.H * DK) + (size_t)h * DK;
@@ -273,8 +356,8 @@ __global__ __launch_bounds__(NTHREADS, 2) void attn_mfma_kernel(Problem pb, Coun
 #pragma unroll
                 for (int r4 = 0; r4 < 4; ++r4) {
                     u32x2 w;
-                    w[0] = pack_bf16(O[db][4 * r4 + 0] * inv, O[db][4 * r4 + 1] * inv);
-                    w[1] = pack_bf16(O[db][4 * r4 + 2] * inv, O[db][4 * r4 + 3] * inv);
+                    w[0] = pack_bf16(st.O[db][4 * r4 + 0] * inv, st.O[db][4 * r4 + 1] * inv);
+                    w[1] = pack_bf16(st.O[db][4 * r4 + 2] * inv, st.O[db][4 * r4 + 3] * inv);
                     *(u32x2*)(orow + 32 * db + 8 * r4 + 4 * g) = w;
                 }
         }
@@ -282,9 +365,10 @@ __global__ __launch_bounds__(NTHREADS, 2) void attn_mfma_kernel(Problem pb, Coun
 
     // one atomic per wavefront
 #pragma unroll
-    for (int o = 32; o > 0; o >>= 1) cnt_logical += __shfl_xor(cnt_logical, o, 64);
+    for (int o = 32; o > 0; o >>= 1) cnt_edge += __shfl_xor(cnt_edge, o, 64);
     if (lane == 0) {
-        if (cnt_logical) atomicAdd(&pb.counters[CNT_LOGICAL], (unsigned long long)cnt_logical);
+        const unsigned long long logical = (unsigned long long)cnt_edge + cnt_interior;
+        if (logical) atomicAdd(&pb.counters[CNT_LOGICAL], logical);
         if (cnt_phys) atomicAdd(&pb.counters[CNT_PHYS], (unsigned long long)cnt_phys);
     }
 }

@@ -82,7 +82,7 @@ def test_symmetric_without_projection():
 @pytest.mark.parametrize("scheme", [FULL, CAUSAL])
 def test_mfma_path_small(shape, scheme):
     B, n, D, H, d, p = shape
-    w = hp.custom_workload("mfma_small", B, n, D, H, d, p, "bf16", scheme, 999 + n)
+    w = hp.custom_workload("mfma_small", B, n, D, H, d, p, "bf16", scheme, 1000 + n)
     _, stats = _run_and_compare(w, scheme, 0.0)
     assert (stats["phys_br"], stats["phys_bc"]) == (32, 32)
     lens = np.random.default_rng(n + 1).integers(1, n + 1, B).astype(np.int32)
