@@ -200,6 +200,192 @@ __global__ __launch_bounds__(256) void proj_mfma_kernel(int Bsz, int N, int Npad
     }
 }
 
+// ---------------------------------------------------------------------------
+// The same GEMM for d_model a multiple of 64, with the k slices copied from
+// global memory straight into LDS (global_load_lds, 16 bytes per lane).  LDS
+// rows are 128 bytes (64 bf16), unpadded; the eight 16-byte chunks of a row are
+// XOR-swizzled with bits 1..3 of the row index, which makes the 128-bit operand
+// reads of 16 consecutive rows conflict-free.  WR x WC wavefronts share a
+// BT x BT tile; fragments of the next k-step are read while the MFMAs of the
+// current one run.
+// ---------------------------------------------------------------------------
+template <int BT, int WR, int WC>
+__global__ __launch_bounds__(64 * WR * WC, (WR * WC) / 4 * (BT == 256 ? 1 : 2))
+void proj_dma_kernel(int Bsz, int N, int Npad, int D, int H, int d, const bf16_t* __restrict__ X,
+                     const bf16_t* __restrict__ Wt, bf16_t* __restrict__ qo, bf16_t* __restrict__ ko,
+                     bf16_t* __restrict__ vto, int tiles_x, int tiles_w)
+{
+    constexpr int NW = WR * WC;
+    constexpr int TA = BT / WR, TB = BT / WC;    // wavefront tile: TA rows of the A side, TB of the B side
+    constexpr int NA = TA / 32, NBK = TB / 32;   // MFMA blocks per edge
+    constexpr int SIDE = BT * 128;               // bytes of one operand side per stage
+    constexpr int STAGE = 2 * SIDE;
+    constexpr int PPW = (BT / 8) / NW;           // 1 KiB pieces (8 rows) per wavefront and side
+    __shared__ __attribute__((aligned(1024))) unsigned char lds[2 * STAGE];
+
+    const int tid = threadIdx.x;
+    const int lane = tid & 63, ln = lane & 31, g = lane >> 5;
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+    const int wr = wave / WC, wc = wave % WC;
+    const int HD = H * d;
+
+    const int n_tiles = tiles_x * tiles_w;
+    const int per_xcd = gridDim.x >> 3;
+    const int tile_id = (blockIdx.x & 7) * per_xcd + (blockIdx.x >> 3);
+    if (tile_id >= n_tiles) return;
+    const int tw = tile_id / tiles_x, tx_ = tile_id - tw * tiles_x;
+    const int x0 = tx_ * BT, w0 = tw * BT;
+    const bool is_v = w0 >= 2 * HD;
+
+    // Source element offsets of this lane for its pieces (piece m = wave + NW*u holds rows 8m..8m+7;
+    // the lane lands at row 8m + lane/8, chunk position lane%8, and fetches the chunk that the
+    // swizzle puts there).
+    unsigned xoff[PPW], woff[PPW];
+#pragma unroll
+    for (int u = 0; u < PPW; ++u) {
+        const int row = (wave + NW * u) * 8 + (lane >> 3);
+        const int c = (lane & 7) ^ ((row >> 1) & 7);
+        const int xr = x0 + row;
+        const int bb = xr / Npad;
+        int i = xr - bb * Npad;
+        i = i < N ? i : N - 1;
+        xoff[u] = (unsigned)(bb * N + i) * (unsigned)D + c * 8;
+        woff[u] = (unsigned)(w0 + row) * (unsigned)D + c * 8;
+    }
+    const int x_side = is_v ? 0 : SIDE, w_side = is_v ? SIDE : 0;
+    auto issue = [&](int k0, int stage) {
+        unsigned char* base = lds + stage * STAGE;
+#pragma unroll
+        for (int u = 0; u < PPW; ++u) {
+            const int m = wave + NW * u;
+            __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void*)(X + (size_t)xoff[u] + k0),
+                                             (__attribute__((address_space(3))) void*)(base + x_side + m * 1024), 16,
+                                             0, 0);
+            __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void*)(Wt + (size_t)woff[u] + k0),
+                                             (__attribute__((address_space(3))) void*)(base + w_side + m * 1024), 16,
+                                             0, 0);
+        }
+    };
+
+    // LDS byte offsets of this lane's operand reads for the four k-steps of a slice, both stages.
+    int aoff[2][4], boff[2][4];
+#pragma unroll
+    for (int st = 0; st < 2; ++st)
+#pragma unroll
+        for (int ks = 0; ks < 4; ++ks) {
+            const int sw = ((2 * ks + g) ^ ((ln >> 1) & 7)) * 16;
+            aoff[st][ks] = st * STAGE + (wr * TA + ln) * 128 + sw;
+            boff[st][ks] = st * STAGE + SIDE + (wc * TB + ln) * 128 + sw;
+        }
+
+    f32x16 acc[NA][NBK];
+#pragma unroll
+    for (int a = 0; a < NA; ++a)
+#pragma unroll
+        for (int b = 0; b < NBK; ++b)
+#pragma unroll
+            for (int r = 0; r < 16; ++r) acc[a][b][r] = 0.f;
+
+    auto compute = [&](const int (&ao)[4], const int (&bo)[4]) {
+        u32x4 af[2][NA], bf[2][NBK];
+#pragma unroll
+        for (int a = 0; a < NA; ++a) af[0][a] = *(const u32x4*)(lds + ao[0] + a * 4096);
+#pragma unroll
+        for (int b = 0; b < NBK; ++b) bf[0][b] = *(const u32x4*)(lds + bo[0] + b * 4096);
+#pragma unroll
+        for (int ks = 0; ks < 4; ++ks) {
+            const int cur = ks & 1, nxt = cur ^ 1;
+            if (ks < 3) {
+#pragma unroll
+                for (int a = 0; a < NA; ++a) af[nxt][a] = *(const u32x4*)(lds + ao[ks + 1] + a * 4096);
+#pragma unroll
+                for (int b = 0; b < NBK; ++b) bf[nxt][b] = *(const u32x4*)(lds + bo[ks + 1] + b * 4096);
+            }
+#pragma unroll
+            for (int a = 0; a < NA; ++a)
+#pragma unroll
+                for (int b = 0; b < NBK; ++b) acc[a][b] = mfma32(af[cur][a], bf[cur][b], acc[a][b]);
+        }
+    };
+
+    const int nk = D / 64;
+    issue(0, 0);
+    __builtin_amdgcn_s_waitcnt(0x0F70);  // vmcnt(0)
+    __syncthreads();
+#pragma nounroll
+    for (int it = 0; it < nk; it += 2) {
+        if (it + 1 < nk) issue((it + 1) * 64, 1);
+        compute(aoff[0], boff[0]);
+        __builtin_amdgcn_s_waitcnt(0x0F70);
+        __syncthreads();
+        if (it + 1 < nk) {
+            if (it + 2 < nk) issue((it + 2) * 64, 0);
+            compute(aoff[1], boff[1]);
+            __builtin_amdgcn_s_waitcnt(0x0F70);
+            __syncthreads();
+        }
+    }
+
+    // Epilogue.  acc[a][b][r]: A-side row wr*TA + 32a + acc_row(r,g), B-side row wc*TB + 32b + ln.
+    if (!is_v) {
+#pragma unroll
+        for (int b = 0; b < NBK; ++b) {
+            const int xr = x0 + wc * TB + 32 * b + ln;
+            const int bb = xr / Npad;
+            const int i = xr - bb * Npad;
+            if (i >= N) continue;
+#pragma unroll
+            for (int a = 0; a < NA; ++a)
+#pragma unroll
+                for (int r4 = 0; r4 < 4; ++r4) {
+                    const int col = w0 + wr * TA + 32 * a + 8 * r4 + 4 * g;
+                    const int which = col >= HD ? 1 : 0;
+                    const int cc = col - which * HD;
+                    const int h = cc / d, l = cc - h * d;
+                    bf16_t* dst = (which ? ko : qo) + (((size_t)bb * H + h) * Npad + i) * d + l;
+                    u32x2 w;
+                    w[0] = pack_bf16(acc[a][b][4 * r4 + 0], acc[a][b][4 * r4 + 1]);
+                    w[1] = pack_bf16(acc[a][b][4 * r4 + 2], acc[a][b][4 * r4 + 3]);
+                    *(u32x2*)dst = w;
+                }
+        }
+    } else {
+#pragma unroll
+        for (int b = 0; b < NBK; ++b) {
+            const int cc = w0 - 2 * HD + wc * TB + 32 * b + ln;
+            const int h = cc / d, l = cc - h * d;
+#pragma unroll
+            for (int a = 0; a < NA; ++a)
+#pragma unroll
+                for (int r4 = 0; r4 < 4; ++r4) {
+                    const int xr = x0 + wr * TA + 32 * a + 8 * r4 + 4 * g;
+                    const int bb = xr / Npad;
+                    const int i = xr - bb * Npad;
+                    if (i >= N) continue;
+                    const int blk = i >> 6, r64 = i & 63;
+                    const int slot = (r64 & 48) | vt_slot16(r64 & 15);
+                    bf16_t* dst = vto + ((((size_t)bb * H + h) * (Npad >> 6) + blk) * d + l) * 64 + slot;
+                    u32x2 w;
+                    w[0] = pack_bf16(acc[a][b][4 * r4 + 0], acc[a][b][4 * r4 + 1]);
+                    w[1] = pack_bf16(acc[a][b][4 * r4 + 2], acc[a][b][4 * r4 + 3]);
+                    *(u32x2*)dst = w;
+                }
+        }
+    }
+}
+
+template <int BT, int WR, int WC>
+hipError_t launch_dma(const Problem& pb, const bf16_t* X, const bf16_t* Wt, bf16_t* q, bf16_t* k, bf16_t* vt,
+                      hipStream_t s)
+{
+    const int tiles_x = pb.B * pb.Npad / BT;
+    const int tiles_w = 3 * pb.H * pb.d / BT;
+    const int grid = ((tiles_x * tiles_w + 7) / 8) * 8;
+    hipLaunchKernelGGL((proj_dma_kernel<BT, WR, WC>), dim3(grid), dim3(64 * WR * WC), 0, s, pb.B, pb.N, pb.Npad, pb.D,
+                       pb.H, pb.d, X, Wt, q, k, vt, tiles_x, tiles_w);
+    return hipGetLastError();
+}
+
 template <int BT>
 hipError_t launch_bt(const Problem& pb, const bf16_t* X, const bf16_t* Wt, bf16_t* q, bf16_t* k, bf16_t* vt,
                      hipStream_t s)
@@ -230,8 +416,12 @@ hipError_t launch_proj_mfma(const Problem& pb, const bf16_t* X, const bf16_t* Wt
     // mixes q, k and v columns) and still gives every CU a few tiles.
     const int HD = pb.H * pb.d;
     const long rows = (long)pb.B * pb.Npad;
-    if (HD % 256 == 0 && rows % 256 == 0 && (rows / 256) * (3L * HD / 256) >= 512)
-        return launch_bt<256>(pb, X, Wt, q, k, vt, s);
+    const bool big = HD % 256 == 0 && rows % 256 == 0 && (rows / 256) * (3L * HD / 256) >= 512;
+    if (pb.D % 64 == 0) {  // k slices go straight to LDS
+        if (big) return launch_dma<256, 2, 4>(pb, X, Wt, q, k, vt, s);
+        if (HD % 128 == 0) return launch_dma<128, 2, 2>(pb, X, Wt, q, k, vt, s);
+    }
+    if (big) return launch_bt<256>(pb, X, Wt, q, k, vt, s);
     if (HD % 128 == 0) return launch_bt<128>(pb, X, Wt, q, k, vt, s);
     return launch_bt<64>(pb, X, Wt, q, k, vt, s);
 }
