@@ -50,6 +50,23 @@ __global__ __launch_bounds__(256) void transpose_w_kernel(int D, int HD, const b
 constexpr int BK = 64;
 constexpr int ROWB = BK * 2 + 16;  // LDS bytes per tile row (padded)
 
+// Tile order.  Workgroup ids are dealt round-robin to the 8 XCDs, so each XCD is
+// given a contiguous run of tile numbers; within the run, tiles are walked in
+// groups of GROUP_W weight tiles by all x tiles, weight tile fastest, so that the
+// ~32 tiles in flight on one XCD form a 4 x 8 patch that shares its operand
+// slices in that XCD's L2 instead of fetching 32 different x slices.
+constexpr int GROUP_W = 4;
+__device__ __forceinline__ void tile_of(int id, int tiles_x, int tiles_w, int& tw, int& tx)
+{
+    const int width = GROUP_W * tiles_x;
+    const int grp = id / width;
+    const int first_w = grp * GROUP_W;
+    const int gsz = min(tiles_w - first_w, GROUP_W);
+    const int local = id - grp * width;
+    tx = local / gsz;
+    tw = first_w + (local - tx * gsz);
+}
+
 template <int BT>
 __global__ __launch_bounds__(256) void proj_mfma_kernel(int Bsz, int N, int Npad, int D, int H, int d,
                                                         const bf16_t* __restrict__ X,
@@ -69,13 +86,12 @@ __global__ __launch_bounds__(256) void proj_mfma_kernel(int Bsz, int N, int Npad
     const int wr = wave >> 1, wc = wave & 1;
     const int HD = H * d;
 
-    // XCD-aware order: each XCD gets a contiguous run of tiles, walked with the
-    // x-side tile fastest so that a weight tile stays in that XCD's L2.
     const int n_tiles = tiles_x * tiles_w;
     const int per_xcd = gridDim.x >> 3;
     const int tile_id = (blockIdx.x & 7) * per_xcd + (blockIdx.x >> 3);
     if (tile_id >= n_tiles) return;
-    const int tw = tile_id / tiles_x, tx_ = tile_id - tw * tiles_x;
+    int tw, tx_;
+    tile_of(tile_id, tiles_x, tiles_w, tw, tx_);
     const int x0 = tx_ * BT;   // first x-side row (padded vector index)
     const int w0 = tw * BT;    // first stacked output column
     const bool is_v = w0 >= 2 * HD;
@@ -233,7 +249,8 @@ void proj_dma_kernel(int Bsz, int N, int Npad, int D, int H, int d, const bf16_t
     const int per_xcd = gridDim.x >> 3;
     const int tile_id = (blockIdx.x & 7) * per_xcd + (blockIdx.x >> 3);
     if (tile_id >= n_tiles) return;
-    const int tw = tile_id / tiles_x, tx_ = tile_id - tw * tiles_x;
+    int tw, tx_;
+    tile_of(tile_id, tiles_x, tiles_w, tw, tx_);
     const int x0 = tx_ * BT, w0 = tw * BT;
     const bool is_v = w0 >= 2 * HD;
 
@@ -306,6 +323,19 @@ void proj_dma_kernel(int Bsz, int N, int Npad, int D, int H, int d, const bf16_t
 #pragma unroll
                 for (int b = 0; b < NBK; ++b) acc[a][b] = mfma32(af[cur][a], bf[cur][b], acc[a][b]);
         }
+        // Issue order: the fragment reads of k-step ks+1 are spread between the MFMAs of k-step ks.
+        constexpr int NRD = NA + NBK, NMF = NA * NBK;
+        __builtin_amdgcn_sched_group_barrier(0x100, NRD, 0);
+#pragma unroll
+        for (int ks = 0; ks < 3; ++ks) {
+#pragma unroll
+            for (int r = 0; r < NRD; ++r) {
+                __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
+                __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);
+            }
+            __builtin_amdgcn_sched_group_barrier(0x008, NMF - NRD, 0);
+        }
+        __builtin_amdgcn_sched_group_barrier(0x008, NMF, 0);
     };
 
     const int nk = D / 64;
