@@ -72,6 +72,8 @@ def main():
     ap.add_argument("--warmup", type=int, default=10)
     ap.add_argument("--workload", default="long", help="tiny|encoder|causal|long|padded")
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--tiles", default="auto", choices=["auto", "wide", "narrow"],
+                    help="attention kernel choice (default: the library's own)")
     args = ap.parse_args()
     if args.gpus != 1:
         sys.exit("bench.py: this build runs on one GPU only (no collectives, no sharding); use --gpus 1")
@@ -94,7 +96,8 @@ def main():
     lens_dev = None if lens is None else torch.from_numpy(lens).to(dev)
     out = torch.empty(w.batch, w.n, w.hd, dtype=X.dtype, device=dev)
     dt = ar.ATTN_F32 if w.dtype == "f32" else ar.ATTN_BF16
-    ctx = ar.attn_init(w.batch, w.n, w.d_model, w.n_heads, w.d_k, w.p, dt, 0.0, 0)
+    flags = {"auto": 0, "wide": ar.ATTN_FLAG_WIDE_TILES, "narrow": ar.ATTN_FLAG_NARROW_TILES}[args.tiles]
+    ctx = ar.attn_init(w.batch, w.n, w.d_model, w.n_heads, w.d_k, w.p, dt, 0.0, flags)
     ar.attn_set_key_lengths(ctx, lens_dev)
     stream = torch.cuda.current_stream(dev)
 

@@ -63,7 +63,12 @@ typedef enum { ATTN_F32 = 0, ATTN_BF16 = 1 } attn_dtype;
 /* Debug flag: same kernels, but every tile is visited and redundant pairs are
  * given weight zero by writing -inf into their scores (the practice Sec. 5.1
  * describes).  Outputs must equal those of the skipping run bit for bit. */
-enum { ATTN_FLAG_NO_SKIP = 1u };
+enum { ATTN_FLAG_NO_SKIP = 1u,
+       /* Kernel choice for the bf16 matrix-core path, normally made from the problem size:
+        * WIDE forces the 256-row workgroups whose wavefront groups alternate between softmax
+        * and MFMA phases, NARROW the 128-row workgroups.  Results obey the same bars. */
+       ATTN_FLAG_WIDE_TILES = 2u,
+       ATTN_FLAG_NARROW_TILES = 4u };
 
 typedef struct {
     int32_t batch;     /* >= 1 */

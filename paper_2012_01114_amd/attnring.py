@@ -18,6 +18,8 @@ ATTN_OK, ATTN_ERR_INVALID, ATTN_ERR_SHAPE, ATTN_ERR_UNSUPPORTED, ATTN_ERR_ALLOC,
 ATTN_SCHEME_FULL, ATTN_SCHEME_SYMMETRIC, ATTN_SCHEME_CAUSAL = 0, 1, 2
 ATTN_F32, ATTN_BF16 = 0, 1
 ATTN_FLAG_NO_SKIP = 1
+ATTN_FLAG_WIDE_TILES = 2
+ATTN_FLAG_NARROW_TILES = 4
 
 EXPORTS = ("attn_init", "attn_set_key_lengths", "attn_forward", "attn_stats", "attn_profile",
            "attn_profile_read", "attn_last_error", "attn_destroy")

@@ -19,57 +19,13 @@
 // block: the row maximum and row sum of the online softmax need one cross-lane
 // exchange, and the exponentials, converted to bf16, are already in B-operand
 // layout for O^T += V^T.P^T.
-#include "mfma_common.h"
+#include "attn_common.h"
 
 namespace attnring {
 namespace {
 
 constexpr int BR = 128;  // query rows per workgroup tile
-constexpr int BC = 64;   // keys per staged block
 constexpr int NTHREADS = 256;
-
-struct CountCfg {
-    int b;        // rows per logical PE
-    int b_shift;  // log2(b), or -1 when b is not a power of two
-};
-
-// ceil(x / b): the number of multiples of b in [0, x)
-__device__ __forceinline__ unsigned cdiv_b(unsigned x, const CountCfg& cc)
-{
-    const unsigned y = x + (unsigned)cc.b - 1u;
-    return cc.b_shift >= 0 ? (y >> cc.b_shift) : y / (unsigned)cc.b;
-}
-__device__ __forceinline__ bool is_multiple(int x, const CountCfg& cc)
-{
-    return cc.b_shift >= 0 ? (x & (cc.b - 1)) == 0 : (x % cc.b) == 0;
-}
-
-// Swizzled chunk position inside an LDS row of ROWB bytes (256 or 128).
-template <int ROWB>
-__device__ __forceinline__ int swz(int chunk, int row)
-{
-    return ROWB == 256 ? (chunk ^ (row & 15)) : (chunk ^ ((row >> 1) & 7));
-}
-
-// One wavefront copies 1 KiB pieces of a [rows][ROWB] tile from global memory to
-// LDS: piece m holds rows m*RPP .. ; lane L lands at byte 16*L of the piece and
-// fetches the chunk that belongs there under the swizzle.
-template <int ROWB>
-__device__ __forceinline__ void dma_pieces(const unsigned char* __restrict__ gsrc, unsigned char* ldst, int first,
-                                           int count, int step, int lane)
-{
-    constexpr int CPR = ROWB / 16;  // chunks per row
-    constexpr int RPP = 64 / CPR;   // rows per piece
-    const int rl = lane / CPR, p = lane % CPR;
-#pragma unroll
-    for (int u = 0; u < count; ++u) {
-        const int m = first + u * step;
-        const int row = m * RPP + rl;
-        const int c = swz<ROWB>(p, row);
-        __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void*)(gsrc + row * ROWB + c * 16),
-                                         (__attribute__((address_space(3))) void*)(ldst + m * 1024), 16, 0, 0);
-    }
-}
 
 template <int DK, bool CAUSAL>
 struct Tile {
@@ -126,15 +82,25 @@ struct Tile {
             }
         }
         // phase 2 (Eq. (2)), online: running maximum and sum per query row
-        float mx = S[0];
+        // The running maximum is the reference of the exponentials.  It is raised only when a
+        // row's scores exceed it by more than 2^RAISE; that is rare after the first blocks, so the
+        // common path has no cross-lane exchange, no accumulator rescale and one exp per pair.
+        float mxl = S[0];
 #pragma unroll
-        for (int r = 1; r < 16; ++r) mx = fmaxf(mx, S[r]);
-        mx = fmaxf(mx, __shfl_xor(mx, 32, 64)) * c2;
-        const bool moved = mx > st.m_run + RAISE;
-        const float m_new = moved ? mx : st.m_run;
-        const float m_use = (MASK && m_new == -INFINITY) ? 0.f : m_new;
-        const float alpha = __builtin_amdgcn_exp2f(st.m_run - m_use);
-        st.m_run = m_new;
+        for (int r = 1; r < 16; ++r) mxl = fmaxf(mxl, S[r]);
+        if (__builtin_amdgcn_ballot_w64(mxl * c2 > st.m_run + RAISE) != 0ull) {
+            const float mx = fmaxf(mxl, __shfl_xor(mxl, 32, 64)) * c2;  // both halves of a row agree
+            const float m_new = mx > st.m_run + RAISE ? mx : st.m_run;
+            const float m_ref = (MASK && m_new == -INFINITY) ? 0.f : m_new;
+            const float alpha = __builtin_amdgcn_exp2f(st.m_run - m_ref);
+            st.m_run = m_new;
+            st.l_run *= alpha;
+#pragma unroll
+            for (int db = 0; db < NDB; ++db)
+#pragma unroll
+                for (int r = 0; r < 16; ++r) st.O[db][r] *= alpha;
+        }
+        const float m_use = (MASK && st.m_run == -INFINITY) ? 0.f : st.m_run;
         float psum = 0.f;
         u32x4 pf[2];
 #pragma unroll
@@ -146,13 +112,7 @@ struct Tile {
                 psum += p0 + p1;
                 pf[hf][w] = pack_bf16(p0, p1);
             }
-        st.l_run = st.l_run * alpha + psum;
-        if (__builtin_amdgcn_ballot_w64(moved) != 0ull) {
-#pragma unroll
-            for (int db = 0; db < NDB; ++db)
-#pragma unroll
-                for (int r = 0; r < 16; ++r) st.O[db][r] *= alpha;
-        }
+        st.l_run += psum;
         __builtin_amdgcn_sched_barrier(0);
         // phase 3 (Eq. (3)): O^T[col][query] += sum_key V^T[col][key] P^T[key][query]
 #pragma unroll
@@ -205,6 +165,9 @@ __global__ __launch_bounds__(NTHREADS, 2) void attn_mfma_kernel(Problem pb, Coun
     for (int ks = 0; ks < NKS; ++ks) koff[ks] = ln * T::KROWB + swz<T::KROWB>(2 * ks + g, ln) * 16;
 #pragma unroll
     for (int ch = 0; ch < 4; ++ch) voff[ch] = T::K_BYTES + ln * (BC * 2) + swz<BC * 2>(2 * ch + g, ln) * 16;
+
+    const unsigned k_lane_off = dma_lane_offset<T::KROWB>(wave, lane);
+    const unsigned v_lane_off = dma_lane_offset<BC * 2>(wave, lane);
 
     unsigned cnt_edge = 0;      // logical tiles found lane by lane in edge blocks
     unsigned cnt_interior = 0;  // logical tiles of fully allowed blocks (wave-uniform)
@@ -278,8 +241,8 @@ __global__ __launch_bounds__(NTHREADS, 2) void attn_mfma_kernel(Problem pb, Coun
 
             auto issue_loads = [&](int J, int buf) {
                 unsigned char* base = lds + buf * T::STAGE;
-                dma_pieces<T::KROWB>(kh + (size_t)J * T::K_BYTES, base, wave, KPIECES, 4, lane);
-                dma_pieces<BC * 2>(vh + (size_t)J * T::V_BYTES, base + T::K_BYTES, wave, VPIECES, 4, lane);
+                dma_pieces<KPIECES>(kh + (size_t)J * T::K_BYTES, base, k_lane_off, wave, 4);
+                dma_pieces<VPIECES>(vh + (size_t)J * T::V_BYTES, base + T::K_BYTES, v_lane_off, wave, 4);
             };
 
             issue_loads(block_of_step(0), 0);

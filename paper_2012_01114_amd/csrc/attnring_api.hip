@@ -130,12 +130,15 @@ attn_status attn_init(const attn_config* cfg, attn_ctx** out_ctx)
         return fail(nullptr, ATTN_ERR_INVALID, "attn_init: every size must be >= 1%s");
     if (cfg->dtype != ATTN_F32 && cfg->dtype != ATTN_BF16)
         return fail(nullptr, ATTN_ERR_INVALID, "attn_init: unknown dtype%s");
-    if (cfg->flags & ~(uint32_t)ATTN_FLAG_NO_SKIP) return fail(nullptr, ATTN_ERR_INVALID, "attn_init: unknown flag%s");
+    if (cfg->flags & ~(uint32_t)(ATTN_FLAG_NO_SKIP | ATTN_FLAG_WIDE_TILES | ATTN_FLAG_NARROW_TILES))
+        return fail(nullptr, ATTN_ERR_INVALID, "attn_init: unknown flag%s");
+    if ((cfg->flags & ATTN_FLAG_WIDE_TILES) && (cfg->flags & ATTN_FLAG_NARROW_TILES))
+        return fail(nullptr, ATTN_ERR_INVALID, "attn_init: WIDE_TILES and NARROW_TILES exclude each other%s");
     if (!(cfg->scale == cfg->scale) || std::isinf(cfg->scale))
         return fail(nullptr, ATTN_ERR_INVALID, "attn_init: scale is not finite%s");
     if (cfg->n % cfg->p != 0)
         return fail(nullptr, ATTN_ERR_SHAPE, "attn_init: n must be divisible by p (ring partitions)%s");
-    const long long Npad = ((long long)cfg->n + 127) / 128 * 128;
+    const long long Npad = ((long long)cfg->n + 255) / 256 * 256;
     const long long hd = (long long)cfg->n_heads * cfg->d_k;
     const long long limit = 0x7fffffffLL;
     if ((long long)cfg->batch * Npad * hd > limit || (long long)cfg->batch * cfg->n * cfg->d_model > limit ||
@@ -248,8 +251,11 @@ attn_status attn_forward(attn_ctx* ctx, const void* X, const void* Wq, const voi
         e = launch_proj_mfma(pb, (const bf16_t*)X, ctx->wt, ctx->qb, ctx->kb, ctx->vtb, s);
         CHECK("launch proj_mfma");
         MARK(2);
-        e = launch_attn_mfma(pb, ctx->qb, ctx->kb, ctx->vtb, (bf16_t*)out, s);
-        CHECK("launch attn_mfma");
+        // The 256-row alternating-phase kernel is chosen by flag only.
+        const bool wide = (cf.flags & ATTN_FLAG_WIDE_TILES) != 0;
+        if (wide) e = launch_attn_pingpong(pb, ctx->qb, ctx->kb, ctx->vtb, (bf16_t*)out, s);
+        else e = launch_attn_mfma(pb, ctx->qb, ctx->kb, ctx->vtb, (bf16_t*)out, s);
+        CHECK("launch attention (mfma)");
         MARK(3);
         ctx->last_proj_gemms = 3;
         ctx->last_phys = MFMA_BLOCK;

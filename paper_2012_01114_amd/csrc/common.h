@@ -15,7 +15,7 @@ enum { SCHEME_FULL = 0, SCHEME_SYMMETRIC = 1, SCHEME_CAUSAL = 2 };
 struct Problem {
     int B, N, D, H, d;   // batch, vectors, d_model, heads, d_k
     int P, b;            // ring partitions and rows per partition (b = N / P)
-    int Npad;            // row pitch of the projected bf16 q/k/v (multiple of 128)
+    int Npad;            // row pitch of the projected bf16 q/k/v (multiple of 256)
     float scale;         // multiplies the raw scores
     int scheme;
     bool noskip;         // debug: visit every tile, mask with -inf
@@ -44,7 +44,11 @@ hipError_t launch_proj_mfma(const Problem& pb, const bf16_t* X, const bf16_t* Wt
                             bf16_t* vt, hipStream_t s);
 hipError_t launch_attn_mfma(const Problem& pb, const bf16_t* q, const bf16_t* k, const bf16_t* vt,
                             bf16_t* out, hipStream_t s);
-// Physical score-block edge of the MFMA attention kernel (phys_br = phys_bc).
+// Same computation for long sequences: 256-row workgroups whose two wavefront groups
+// alternate between the softmax and the MFMA phases.
+hipError_t launch_attn_pingpong(const Problem& pb, const bf16_t* q, const bf16_t* k, const bf16_t* vt,
+                                bf16_t* out, hipStream_t s);
+// Physical score-block edge of the MFMA attention kernels (phys_br = phys_bc).
 enum { MFMA_BLOCK = 32 };
 
 }  // namespace attnring

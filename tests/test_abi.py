@@ -48,6 +48,7 @@ def _init(**kw):
     (dict(batch=-1), ar.ATTN_ERR_INVALID),
     (dict(dtype=7), ar.ATTN_ERR_INVALID),
     (dict(flags=8), ar.ATTN_ERR_INVALID),
+    (dict(flags=6), ar.ATTN_ERR_INVALID),
     (dict(scale=float("nan")), ar.ATTN_ERR_INVALID),
     (dict(n=18, p=4), ar.ATTN_ERR_SHAPE),          # n must be divisible by the ring partitions
     (dict(batch=4096, n=65536, n_heads=64, p=1), ar.ATTN_ERR_SHAPE),

@@ -14,7 +14,7 @@ pytestmark = pytest.mark.gpu
 FULL, SYM, CAUSAL = inputs.SCHEME_FULL, inputs.SCHEME_SYMMETRIC, inputs.SCHEME_CAUSAL
 
 
-def _run_and_compare(w, scheme, scale=0.0, lens=None, zero_wq=False, sym_no_proj=False):
+def _run_and_compare(w, scheme, scale=0.0, lens=None, zero_wq=False, sym_no_proj=False, flags=0):
     print(f"[case] {w.name} B{w.batch} N{w.n} D{w.d_model} H{w.n_heads} d{w.d_k} P{w.p} {w.dtype} "
           f"scheme={scheme} scale={scale} lens={'yes' if lens is not None else 'no'}", flush=True)
     stored, f64 = inputs.make_inputs(w, zero_wq=zero_wq)
@@ -23,7 +23,7 @@ def _run_and_compare(w, scheme, scale=0.0, lens=None, zero_wq=False, sym_no_proj
         stored["Wq"] = f64["Wq"] = None
     if scheme == SYM:
         stored["Wk"] = stored["Wv"] = None
-    run = hp.GpuRun(w, stored, scale=scale)
+    run = hp.GpuRun(w, stored, scale=scale, flags=flags)
     try:
         got, stats = run.forward(scheme)
     finally:
@@ -78,28 +78,32 @@ def test_symmetric_without_projection():
     (2, 384, 128, 2, 128, 12),    # d_k = 128, partitions of 32 rows
     (1, 136, 72, 1, 128, 17),     # d_model not a multiple of 64 (k tail)
     (1, 520, 64, 2, 64, 5),       # partitions larger than a score block (104 rows)
+    (1, 1096, 64, 1, 128, 137),   # several 256-row tiles and a ragged tail
 ])
 @pytest.mark.parametrize("scheme", [FULL, CAUSAL])
-def test_mfma_path_small(shape, scheme):
+@pytest.mark.parametrize("tiles", [ar.ATTN_FLAG_NARROW_TILES, ar.ATTN_FLAG_WIDE_TILES])
+def test_mfma_path_small(shape, scheme, tiles):
     B, n, D, H, d, p = shape
     w = hp.custom_workload("mfma_small", B, n, D, H, d, p, "bf16", scheme, 1000 + n)
-    _, stats = _run_and_compare(w, scheme, 0.0)
+    _, stats = _run_and_compare(w, scheme, 0.0, flags=tiles)
     assert (stats["phys_br"], stats["phys_bc"]) == (32, 32)
     lens = np.random.default_rng(n + 1).integers(1, n + 1, B).astype(np.int32)
     lens[-1] = n // 2 + 3
-    _run_and_compare(w, scheme, 0.0, lens=lens)
-    _run_and_compare(w, scheme, 0.0, lens=np.zeros(B, dtype=np.int32))
+    _run_and_compare(w, scheme, 0.0, lens=lens, flags=tiles)
+    _run_and_compare(w, scheme, 0.0, lens=np.zeros(B, dtype=np.int32), flags=tiles)
 
 
 # ---- the -inf practice (Sec. 5.1) against skipping: identical bits ------------------------------
 @pytest.mark.parametrize("case", [
-    ("f32", 1, 48, 32, 2, 16, 6),
-    ("bf16", 2, 320, 64, 2, 64, 40),
-    ("bf16", 1, 264, 64, 1, 128, 33),
+    ("f32", 1, 48, 32, 2, 16, 6, 0),
+    ("bf16", 2, 320, 64, 2, 64, 40, ar.ATTN_FLAG_NARROW_TILES),
+    ("bf16", 1, 264, 64, 1, 128, 33, ar.ATTN_FLAG_NARROW_TILES),
+    ("bf16", 2, 704, 64, 2, 64, 88, ar.ATTN_FLAG_WIDE_TILES),
+    ("bf16", 1, 520, 64, 1, 128, 65, ar.ATTN_FLAG_WIDE_TILES),
 ])
 @pytest.mark.parametrize("scheme", [FULL, SYM, CAUSAL])
 def test_skip_equals_noskip_bits(case, scheme):
-    dtype, B, n, D, H, d, p = case
+    dtype, B, n, D, H, d, p, tiles = case
     w = hp.custom_workload("bits", B, n, D, H, d, p, dtype, scheme, 31 + n)
     stored, _ = inputs.make_inputs(w)
     lens = None
@@ -108,7 +112,7 @@ def test_skip_equals_noskip_bits(case, scheme):
     stored["lens"] = lens
     outs = []
     for flags in (0, ar.ATTN_FLAG_NO_SKIP):
-        run = hp.GpuRun(w, stored, flags=flags)
+        run = hp.GpuRun(w, stored, flags=flags | tiles)
         try:
             got, stats = run.forward(scheme)
         finally:
