@@ -39,14 +39,17 @@ def needed_pairs(w, lens):
     return sum(per) * w.n_heads
 
 
-def cpu_baseline(w, f64, lens, budget_heads):
-    """Time the CPU checker on `budget_heads` (batch, head) pairs, 256 sampled rows each."""
+def cpu_baseline(w, f64, lens, budget_s=12.0, max_heads=256):
+    """Time the CPU checker on (batch, head) pairs, 256 sampled rows each, until about
+    `budget_s` seconds of CPU work have been spent."""
     from oracle import attn_oracle as orc
     import numpy as np
     rng = np.random.default_rng(7)
     t_total, flop = 0.0, 0.0
     picks = []
-    for s in range(budget_heads):
+    for s in range(max_heads):
+        if t_total >= budget_s:
+            break
         b = int(rng.integers(0, w.batch))
         h = int(rng.integers(0, w.n_heads))
         rows = sorted(int(r) for r in rng.choice(w.n, size=min(256, w.n), replace=False))
@@ -61,7 +64,7 @@ def cpu_baseline(w, f64, lens, budget_heads):
         picks.append((b, h))
     return {"value": flop / t_total / 1e12, "unit": "TFLOP/s", "cores": orc.num_threads(), "kind": "oracle",
             "seconds": round(t_total, 2),
-            "sample": f"{budget_heads} (batch, head) pairs, k and v projected for all {w.n} rows, "
+            "sample": f"{len(picks)} (batch, head) pairs, k and v projected for all {w.n} rows, "
                       f"{min(256, w.n)} random query rows each; FLOPs counted for the sample only"}
 
 
@@ -74,7 +77,19 @@ def main():
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--tiles", default="auto", choices=["auto", "wide", "narrow"],
                     help="attention kernel choice (default: the library's own)")
+    ap.add_argument("--copy-probe", type=int, default=0, metavar="MIB",
+                    help="instead of the benchmark, run 10 plain device copies of MIB MiB (reference for "
+                         "scaling rocprofv3 FETCH_SIZE / WRITE_SIZE readings)")
     args = ap.parse_args()
+    if args.copy_probe:
+        import torch
+        src = torch.ones(args.copy_probe << 20, dtype=torch.uint8, device="cuda:0")
+        dst = torch.empty_like(src)
+        for _ in range(10):
+            dst.copy_(src)
+        torch.cuda.synchronize()
+        print(json.dumps({"copy_probe_mib": args.copy_probe, "copies": 10}))
+        return
     if args.gpus != 1:
         sys.exit("bench.py: this build runs on one GPU only (no collectives, no sharding); use --gpus 1")
 
@@ -154,7 +169,7 @@ def main():
     torch.cuda.synchronize()
     ar.attn_destroy(ctx)
     if not args.no_cpu_baseline:
-        line["cpu_baseline"] = cpu_baseline(w, f64, lens, budget_heads=8 if w.name == "long" else 16)
+        line["cpu_baseline"] = cpu_baseline(w, f64, lens)
     print(json.dumps(line))
 
 
