@@ -64,9 +64,9 @@ typedef enum { ATTN_F32 = 0, ATTN_BF16 = 1 } attn_dtype;
  * given weight zero by writing -inf into their scores (the practice Sec. 5.1
  * describes).  Outputs must equal those of the skipping run bit for bit. */
 enum { ATTN_FLAG_NO_SKIP = 1u,
-       /* Kernel choice for the bf16 matrix-core path, normally made from the problem size:
-        * WIDE forces the 256-row workgroups whose wavefront groups alternate between softmax
-        * and MFMA phases, NARROW the 128-row workgroups.  Results obey the same bars. */
+       /* Workgroup shape of the bf16 matrix-core path for d_k = 64, normally 128 query rows
+        * (4 wavefronts): WIDE asks for 256 rows (8 wavefronts), NARROW for 128.  d_k = 128
+        * always takes 256 rows.  Results obey the same bars. */
        ATTN_FLAG_WIDE_TILES = 2u,
        ATTN_FLAG_NARROW_TILES = 4u };
 

@@ -1,0 +1,473 @@
+// Fused phases 1-3 (Sec. 3.1, Eq. (1)-(3)) on the bf16 matrix cores of gfx950,
+// FULL and masked scheme, scheduled so that the two wavefronts that share a SIMD
+// keep its matrix cores and its vector ALUs busy at the same time.
+//
+// Ring mapping.  A wavefront owns 32 consecutive query rows (one or several of
+// the paper's PEs, which own n/P rows each); WAVES wavefronts form a workgroup.
+// The workgroup meets the 64-key tiles of its head in ring order, starting with
+// the tile at its own diagonal and walking down, wrapping round for the FULL
+// scheme; tiles with no needed pair are not in the walk, and a wavefront joins
+// the walk at the first 32-key block that holds a pair it needs (Sec. 5.1:
+// masked pairs are left out of all three phases).  Masked scheme: workgroup x
+// handles row tiles T-1-x and x, the packing of row n-i with row i that
+// equalises the work per PE (Sec. 5.2).
+//
+// Schedule.  The walk is cut into 32-key blocks; for block n a wavefront runs
+//     E(n)  vector ALUs :  pair tests of an edge block, P(n) = exp2(S(n) - ref), row sums
+//                          (phase 2, Eq. (2)); first of all it requests from LDS the
+//                          fragments M(n) will take: V^T of block n, K of block n+1
+//     M(n)  matrix cores:  O += V(n)^T.P(n)^T (phase 3, Eq. (3)),
+//                          S(n+1) = K(n+1).Q^T (phase 1 of the next block, Eq. (1))
+// in the order E(n), M(n), E(n+1), ...  A workgroup of eight wavefronts has two
+// groups of four; wavefronts w and w+4 share a SIMD.  Group 0 meets the per-tile
+// workgroup barrier in front of E(2t), group 1 between E(2t) and M(2t): after
+// every barrier one group is in a vector phase while the other is in a matrix
+// phase, and they stay half an iteration apart.  Scores are computed transposed
+// (S^T = K.Q^T): a lane holds 16 keys of ONE query per 32x32 block, the
+// exponentials, rounded to bf16, are already in B-operand layout for
+// O^T += V^T.P^T, and a row needs no cross-lane traffic on the common path.
+//
+// Online softmax with a lazily raised reference.  q arrives pre-multiplied by
+// scale*log2(e) and the score MFMAs start from minus the row's reference, so the
+// MFMA yields the base-2 exponent itself and an exponential costs one v_exp_f32;
+// row sums take two bf16 weights per v_dot2c.  The reference is raised only when a score
+// exceeds it by more than 2^RAISE (rare after the first blocks); until then
+// exponentials may reach 2^RAISE, which fp32 sums and bf16 operands hold without
+// loss.  Raising rescales the row at the head of E(n), when everything computed
+// with the old reference has been added to O.
+//
+// K[64][d] and V^T[d][64] tiles go from global memory straight into a ring of
+// LDS stages (global_load_lds, 16 bytes per lane) ahead of their use; one
+// workgroup barrier per tile.  LDS rows are unpadded; their 16-byte chunks are
+// XOR-swizzled with the row index (conflict-free 128-bit reads).
+#include <type_traits>
+
+#include "attn_common.h"
+
+namespace attnring {
+namespace {
+
+constexpr float PIPE_RAISE = 8.f;  // slack of the lazy reference, in base-2 exponent units
+
+template <int DK, int WAVES, bool CAUSAL>
+struct Pipe {
+    static constexpr int NKS = DK / 16;         // k-steps of the score product
+    static constexpr int NDB = DK / 32;         // 32-row blocks of O^T
+    static constexpr int KROWB = DK * 2;        // bytes per key row in LDS
+    static constexpr int K_BYTES = BC * KROWB;  // 8 or 16 KiB
+    static constexpr int V_BYTES = DK * BC * 2;
+    static constexpr int STAGE = K_BYTES + V_BYTES;
+    static constexpr int BR = 32 * WAVES;       // rows per workgroup
+    static constexpr int KPIECES = K_BYTES / 1024 / WAVES;  // 1 KiB copy pieces per wavefront and tile
+    static constexpr int VPIECES = V_BYTES / 1024 / WAVES;
+    static constexpr int PPW = KPIECES + VPIECES;
+    // LDS ring, in 64-key tiles.  Three stages let three 4-wavefront workgroups of d_k = 64 share a
+    // CU (three wavefronts per SIMD); otherwise four stages and two wavefronts per SIMD.
+    static constexpr int STAGES = (DK == 64 && WAVES == 4) ? 3 : 4;
+    static constexpr int OCC = (DK == 64 && WAVES == 4) ? 3 : 2;
+
+    struct Row {
+        f32x16 O[NDB];  // O^T, un-normalised
+        f32x16 S;       // base-2 scores, minus the reference, of the block whose phase 2 comes next
+        f32x16 Cneg;    // minus the reference: the C operand the score MFMAs start from
+        u32x4 P[2];     // exponentials of the current block, bf16, B-operand layout
+        float thr;      // RAISE once the row has a reference, -inf before
+        float mref;     // the reference (0 before the row has one)
+        float l;        // this lane's part of the row sum
+    };
+    struct Frags {
+        u32x4 kf[NKS];     // K of block n+1
+        u32x4 vf[2][NDB];  // V^T of block n: keys 0..15 and 16..31 of the block
+    };
+
+    static __device__ __forceinline__ f32x16 zero16()
+    {
+        f32x16 z;
+#pragma unroll
+        for (int e = 0; e < 16; ++e) z[e] = 0.f;
+        return z;
+    }
+    static __device__ __forceinline__ float max16(const f32x16& S)
+    {
+        float m0 = fmaxf(fmaxf(S[0], S[1]), S[2]), m1 = fmaxf(fmaxf(S[3], S[4]), S[5]);
+        float m2 = fmaxf(fmaxf(S[6], S[7]), S[8]), m3 = fmaxf(fmaxf(S[9], S[10]), S[11]);
+        float m4 = fmaxf(fmaxf(S[12], S[13]), S[14]);
+        m0 = fmaxf(fmaxf(m0, m1), m2);
+        m3 = fmaxf(fmaxf(m3, m4), S[15]);
+        return fmaxf(m0, m3);
+    }
+    // Pair test of an edge block: key kb + acc_row(e, g) against the lane's last allowed key.
+    static __device__ __forceinline__ void mask_block(f32x16& S, int lim)
+    {
+#pragma unroll
+        for (int e = 0; e < 16; ++e) S[e] = (8 * (e >> 2) + (e & 3)) <= lim ? S[e] : -INFINITY;
+    }
+    static __device__ __forceinline__ void read_k(Frags& fr, const unsigned char* kblk, const int (&koff)[NKS])
+    {
+#pragma unroll
+        for (int ks = 0; ks < NKS; ++ks) fr.kf[ks] = *(const u32x4*)(kblk + koff[ks]);
+    }
+    static __device__ __forceinline__ void read_v(Frags& fr, const unsigned char* vstage, int voff0, int voff1)
+    {
+#pragma unroll
+        for (int db = 0; db < NDB; ++db) {
+            fr.vf[0][db] = *(const u32x4*)(vstage + voff0 + db * 32 * (BC * 2));
+            fr.vf[1][db] = *(const u32x4*)(vstage + voff1 + db * 32 * (BC * 2));
+        }
+    }
+    // Phase 1 (Eq. (1)) of one block from the K fragments in fr; the accumulator starts at minus
+    // the row's reference, so the result is the exponent phase 2 needs.
+    static __device__ __forceinline__ f32x16 scores(const Row& r, const Frags& fr, const u32x4 (&qf)[NKS])
+    {
+        f32x16 S = mfma32(fr.kf[0], qf[0], r.Cneg);
+#pragma unroll
+        for (int ks = 1; ks < NKS; ++ks) S = mfma32(fr.kf[ks], qf[ks], S);
+        return S;
+    }
+    // Phase 3 (Eq. (3)) of one block from the V^T fragments in fr and the row's exponentials.
+    static __device__ __forceinline__ void weighted_sum(Row& r, const Frags& fr)
+    {
+#pragma unroll
+        for (int hf = 0; hf < 2; ++hf)
+#pragma unroll
+            for (int db = 0; db < NDB; ++db) r.O[db] = mfma32(fr.vf[hf][db], r.P[hf], r.O[db]);
+    }
+
+    // A score beyond the slack (or the first finite score of a row): move the reference to the
+    // row's largest score and rescale what the row has accumulated.
+    static __device__ __forceinline__ void raise_reference(Row& r, float mxl)
+    {
+        asm volatile("" ::: "memory");  // keeps this rare path a branch of its own
+        const float mx = fmaxf(mxl, __shfl_xor(mxl, 32, 64));  // both halves of a row agree
+        const bool raise = mx > r.thr;
+        const bool started = r.thr > -INFINITY;
+        const float delta = raise ? mx : 0.f;
+        const float alpha = (raise && started) ? __builtin_amdgcn_exp2f(-delta) : 1.f;
+        r.mref = raise ? r.mref + delta : r.mref;
+        r.thr = raise ? PIPE_RAISE : r.thr;
+        r.l *= alpha;
+#pragma unroll
+        for (int db = 0; db < NDB; ++db)
+#pragma unroll
+            for (int e = 0; e < 16; ++e) r.O[db][e] *= alpha;
+#pragma unroll
+        for (int e = 0; e < 16; ++e) {
+            r.S[e] -= delta;  // the block at hand was computed against the old reference
+            r.Cneg[e] = -r.mref;
+        }
+    }
+
+    // Phase 2 (Eq. (2)) of the block in r.S; the row sum is normalised at the very end.
+    static __device__ __forceinline__ void exponentials(Row& r)
+    {
+        typedef __bf16 bf16x2 __attribute__((ext_vector_type(2)));
+        const unsigned ones = 0x3f803f80u;  // (1, 1) in bf16
+        float psum = r.l;
+#pragma unroll
+        for (int hf = 0; hf < 2; ++hf)
+#pragma unroll
+            for (int w = 0; w < 4; ++w) {
+                const float p0 = __builtin_amdgcn_exp2f(r.S[8 * hf + 2 * w]);
+                const float p1 = __builtin_amdgcn_exp2f(r.S[8 * hf + 2 * w + 1]);
+                const unsigned pk = pack_bf16(p0, p1);
+                r.P[hf][w] = pk;
+                // the row sum takes the rounded weights, the ones phase 3 multiplies with
+                psum = __builtin_amdgcn_fdot2_f32_bf16(__builtin_bit_cast(bf16x2, pk), __builtin_bit_cast(bf16x2, ones),
+                                                       psum, false);
+            }
+        r.l = psum;
+    }
+};
+
+template <int DK, int WAVES, bool CAUSAL>
+__global__ __launch_bounds__(64 * WAVES)
+__attribute__((amdgpu_waves_per_eu(Pipe<DK, WAVES, CAUSAL>::OCC, Pipe<DK, WAVES, CAUSAL>::OCC)))
+void attn_pipe_kernel(Problem pb, CountCfg cc, const bf16_t* __restrict__ q, const bf16_t* __restrict__ k,
+                      const bf16_t* __restrict__ vt, bf16_t* __restrict__ out, int n_qtiles, int per_head, int n_work)
+{
+    typedef Pipe<DK, WAVES, CAUSAL> T;
+    constexpr int NKS = T::NKS, NDB = T::NDB, BR = T::BR;
+    __shared__ __attribute__((aligned(1024))) unsigned char lds[T::STAGES * T::STAGE];
+
+    const int tid = threadIdx.x;
+    const int lane = tid & 63, ln = lane & 31, g = lane >> 5;
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+    const int grp = WAVES == 8 ? (wave >> 2) : 0;  // which side of the workgroup barrier E(2t) lies on
+
+    // Consecutive workgroup ids go to different XCDs; give each XCD a contiguous
+    // run of work items so that the workgroups of one head share an L2.
+    const int per_xcd = gridDim.x >> 3;
+    const int work = (blockIdx.x & 7) * per_xcd + (blockIdx.x >> 3);
+    if (work >= n_work) return;
+    const int bh = work / per_head;
+    const int x = work - bh * per_head;
+    const int bb = bh / pb.H, h = bh - bb * pb.H;
+
+    const int N = pb.N, Npad = pb.Npad;
+    int len = N;
+    if (pb.lens) { len = pb.lens[bb]; len = len < 0 ? 0 : (len > N ? N : len); }
+    const int nkt_all = Npad / BC;
+
+    const bf16_t* qh = q + (size_t)bh * Npad * DK;
+    const unsigned char* kh = (const unsigned char*)(k + (size_t)bh * Npad * DK);
+    const unsigned char* vh = (const unsigned char*)(vt + (size_t)bh * Npad * DK);
+
+    // Swizzled LDS byte offsets of this lane's operand reads: K rows relative to the first row of
+    // a 32-key block, V^T relative to the stage for the lower 32 keys of a tile (the upper 32 keys
+    // lie 4 chunks further, which under the XOR swizzle is the offset XOR 64).
+    int koff[NKS], voff[2];
+#pragma unroll
+    for (int ks = 0; ks < NKS; ++ks) koff[ks] = ln * T::KROWB + swz<T::KROWB>(2 * ks + g, ln) * 16;
+#pragma unroll
+    for (int hf = 0; hf < 2; ++hf) voff[hf] = T::K_BYTES + ln * (BC * 2) + swz<BC * 2>(2 * hf + g, ln) * 16;
+
+    const unsigned k_lane_off = dma_lane_offset<T::KROWB>(wave, lane);
+    const unsigned v_lane_off = dma_lane_offset<BC * 2>(wave, lane);
+
+    unsigned long long cnt_logical = 0;  // per lane; summed over the wavefront at the end
+    unsigned cnt_phys = 0;               // wave-uniform
+
+    const int n_pass = CAUSAL ? 2 : 1;
+#pragma nounroll
+    for (int pass = 0; pass < n_pass; ++pass) {
+        int I;
+        if (CAUSAL) {
+            I = pass == 0 ? n_qtiles - 1 - x : x;
+            if (pass == 1 && x == n_qtiles - 1 - x) break;
+        } else {
+            I = x;
+        }
+        const int i0w = I * BR + wave * 32;  // first row of this wavefront
+        const int i = i0w + ln;              // this lane's query row
+        const bool wave_active = i0w < N;
+
+        // The walk over 64-key tiles.  Needed tiles are J = 0 .. nJ-1.
+        //   masked scheme: J = Js, Js-1, .., 0 (own diagonal tile first);
+        //   FULL: the tile cut by the key length first (if any), then the whole
+        //         tiles in ring order from the own tile.
+        // In debug mode the tiles with no needed pair are walked first; they change nothing.
+        // Inside a tile the upper 32 keys come first, so key offsets fall along the masked walk.
+        int nJ = (len + BC - 1) / BC;
+        if (CAUSAL) nJ = nJ < (I + 1) * (BR / BC) ? nJ : (I + 1) * (BR / BC);
+        const int n_dead = pb.noskip ? nkt_all - nJ : 0;
+        const int nT = nJ + n_dead;
+        const int has_cut = (!CAUSAL && (len % BC) != 0) ? 1 : 0;
+        const int n_ring = nJ - has_cut;  // FULL: whole tiles
+        const int Jown = (I + 1) * (BR / BC) - 1;
+        const int Js = CAUSAL ? nJ - 1 : (Jown < n_ring ? Jown : n_ring - 1);
+        auto tile_of_step = [&](int t) -> int {
+            if (t < n_dead) return nkt_all - 1 - t;
+            t -= n_dead;
+            if (CAUSAL) return Js - t;
+            if (t < has_cut) return nJ - 1;
+            int J = Js - (t - has_cut);
+            return J < 0 ? J + n_ring : J;
+        };
+        const int NB = 2 * nT;  // 32-key blocks of the walk
+        auto key_of_block = [&](int n) -> int { return tile_of_step(n >> 1) * BC + 32 * (1 - (n & 1)); };
+        auto block_needed = [&](int kb) -> bool { return pb.noskip || (kb < len && (!CAUSAL || kb <= i0w)); };
+        auto block_is_edge = [&](int kb) -> bool {
+            return pb.noskip || kb + 32 > len || (CAUSAL && kb + 31 > i0w);
+        };
+        // The blocks a wavefront leaves out lie at the head of the walk, its edge blocks follow,
+        // the rest are blocks in which every pair is allowed.
+        int n_first = 0;
+        if (!wave_active) n_first = NB;
+        while (n_first < NB && !block_needed(key_of_block(n_first))) ++n_first;
+        int n_edge_end = n_first;
+        while (n_edge_end < NB && block_is_edge(key_of_block(n_edge_end))) ++n_edge_end;
+
+        // ---- counts: logical tiles whose first pair is allowed ----
+        if (n_first < NB) {
+            cnt_phys += (unsigned)(NB - n_first);
+            const unsigned nr_anchor = cdiv_b(min(i0w + 32, N), cc) - cdiv_b(min(i0w, N), cc);
+            if (pb.noskip) {
+                if (lane == 0) cnt_logical += (unsigned long long)nr_anchor * cdiv_b(N, cc);
+            } else {
+                // whole blocks below the diagonal block and below the key length: every pair allowed
+                int k_int = (len >> 5) << 5;
+                if (CAUSAL) k_int = k_int < i0w ? k_int : i0w;
+                if (k_int < 0) k_int = 0;
+                if (lane == 0) cnt_logical += (unsigned long long)nr_anchor * cdiv_b(k_int, cc);
+                // the rest (diagonal block, block cut by the key length): pair by pair
+                const int k_end = CAUSAL ? (len < i0w + 32 ? len : i0w + 32) : len;
+                if (g == 0 && i < N && is_multiple(i, cc)) {
+#pragma nounroll
+                    for (int j = (int)cdiv_b(k_int, cc) * cc.b; j < k_end; j += cc.b)
+                        cnt_logical += (!CAUSAL || j <= i) ? 1u : 0u;
+                }
+            }
+        }
+
+        typename T::Row r;
+#pragma unroll
+        for (int db = 0; db < NDB; ++db) r.O[db] = T::zero16();
+        r.S = T::zero16();
+        r.Cneg = T::zero16();
+        r.P[0] = r.P[1] = u32x4{0u, 0u, 0u, 0u};
+        r.thr = -INFINITY;
+        r.mref = 0.f;
+        r.l = 0.f;
+
+        if (nT > 0) {
+            // Q rows of this wavefront as B operands (rows >= n of the workspace are zero).
+            u32x4 qf[NKS];
+#pragma unroll
+            for (int ks = 0; ks < NKS; ++ks) qf[ks] = *(const u32x4*)(qh + (size_t)i * DK + ks * 16 + g * 8);
+
+            auto issue_tile = [&](int u) {
+                const int J = tile_of_step(u);
+                unsigned char* base = lds + (u % T::STAGES) * T::STAGE;
+                dma_pieces<T::KPIECES>(kh + (size_t)J * T::K_BYTES, base, k_lane_off, wave, WAVES);
+                dma_pieces<T::VPIECES>(vh + (size_t)J * T::V_BYTES, base + T::K_BYTES, v_lane_off, wave, WAVES);
+            };
+            // Start of tile t: tiles t and t+1 are in LDS, every wavefront is done with tile t-1,
+            // whose stage takes tile t+STAGES-1.
+            auto tile_sync = [&](int t) {
+                // tiles t+2 .. t+STAGES-2 may stay in flight
+                if (T::STAGES > 3 && t + 2 < nT) __builtin_amdgcn_s_waitcnt(0x0F70 | ((T::STAGES - 3) * T::PPW));
+                else __builtin_amdgcn_s_waitcnt(0x0F70);  // vmcnt(0)
+                __builtin_amdgcn_s_waitcnt(0xC07F);       // lgkmcnt(0): this wavefront's LDS reads are done
+                __builtin_amdgcn_s_barrier();
+                if (t + T::STAGES - 1 < nT) issue_tile(t + T::STAGES - 1);
+            };
+            // prologue of the ring: the first STAGES-1 tiles requested, tiles 0 and 1 awaited
+            {
+                const int pre = nT < T::STAGES - 1 ? nT : T::STAGES - 1;
+                for (int u = 0; u < pre; ++u) issue_tile(u);
+                tile_sync(0);
+            }
+            // The barrier of tile t (t >= 1) lies in front of E(2t) for group 0 and between E(2t) and
+            // M(2t) for group 1.  A wavefront that joins the walk at block n_first first passes the
+            // barriers that lie in front of E(n_first).
+            int next_sync = 1;
+            {
+                const int upto = grp == 0 ? (n_first >> 1) : ((n_first - 1) >> 1);  // n_first == 0: none
+                for (; next_sync <= upto && next_sync < nT; ++next_sync) tile_sync(next_sync);
+            }
+
+            if (n_first < NB) {
+                typename T::Frags fr;
+                int t = n_first >> 1;
+                // LDS byte offsets of the stages of tile t and of tile t+1, kept by increments
+                constexpr unsigned RING = T::STAGES * T::STAGE;
+                unsigned stg = (unsigned)(t % T::STAGES) * T::STAGE;
+                unsigned stg_n = stg + T::STAGE == RING ? 0u : stg + T::STAGE;
+                // scores of the first block, outside the rotation
+                {
+                    const unsigned char* kblk = lds + stg + (1 - (n_first & 1)) * 32 * T::KROWB;
+                    T::read_k(fr, kblk, koff);
+                    r.S = T::scores(r, fr, qf);
+                }
+                int lim_base = len - 1;  // the lane's last allowed key
+                if (CAUSAL) lim_base = lim_base < i ? lim_base : i;
+                lim_base -= 4 * g;
+
+                // E(n) for the upper (UPPER = 1: first block of a tile) or lower 32 keys of tile t
+                auto phase_e = [&](auto upper, bool masked, int J) {
+                    constexpr int UPPER = decltype(upper)::value;
+                    if (masked) T::mask_block(r.S, lim_base - (J * BC + 32 * UPPER));
+                    const float mxl = T::max16(r.S);
+                    if (__builtin_amdgcn_ballot_w64(mxl > r.thr) != 0ull) T::raise_reference(r, mxl);
+                    // requests first: V^T of this block; K of the next block, which is the lower half of
+                    // this tile or the upper half of the next tile
+                    T::read_v(fr, lds + stg, voff[0] ^ (64 * UPPER), voff[1] ^ (64 * UPPER));
+                    T::read_k(fr, UPPER ? lds + stg : lds + stg_n + 32 * T::KROWB, koff);
+                    __builtin_amdgcn_sched_barrier(0);
+                    T::exponentials(r);
+                };
+                auto phase_m = [&]() {
+                    __builtin_amdgcn_s_setprio(1);
+                    T::weighted_sum(r, fr);
+                    r.S = T::scores(r, fr, qf);  // after the last block: of stale keys, unused
+                    __builtin_amdgcn_s_setprio(0);
+                };
+                auto next_tile = [&]() {
+                    ++t;
+                    stg = stg_n;
+                    stg_n = stg_n + T::STAGE == RING ? 0u : stg_n + T::STAGE;
+                };
+                // tiles [t, t_end): both blocks of each, with the group's barrier position
+                auto run_tiles = [&](int t_end, bool masked) {
+#pragma nounroll
+                    while (t < t_end) {
+                        const int J = masked ? tile_of_step(t) : 0;
+                        if (grp == 0 && t >= next_sync) { tile_sync(t); ++next_sync; }
+                        phase_e(std::integral_constant<int, 1>{}, masked, J);
+                        if (grp == 1 && t >= next_sync) { tile_sync(t); ++next_sync; }
+                        phase_m();
+                        phase_e(std::integral_constant<int, 0>{}, masked, J);
+                        phase_m();
+                        next_tile();
+                    }
+                };
+                // a walk that starts with the lower block of a tile
+                if (n_first & 1) {
+                    const bool masked = n_first < n_edge_end;
+                    phase_e(std::integral_constant<int, 0>{}, masked, masked ? tile_of_step(t) : 0);
+                    phase_m();
+                    next_tile();
+                }
+                const int t_edge_end = (n_edge_end + 1) >> 1;  // tiles that hold an edge block: pair tests
+                run_tiles(t_edge_end < nT ? t_edge_end : nT, true);
+                run_tiles(nT, false);
+            }
+            // keep the ring going to its end (wavefronts that never joined the walk)
+            for (; next_sync < nT; ++next_sync) tile_sync(next_sync);
+            __builtin_amdgcn_s_waitcnt(0xC07F);
+            __builtin_amdgcn_s_barrier();  // the next pass refills the stages
+        }
+
+        // y_i = O_i / l_i ; a row with no allowed pair is zero.
+        const float l_tot = r.l + __shfl_xor(r.l, 32, 64);
+        if (i < N) {
+            const float inv = l_tot > 0.f ? 1.f / l_tot : 0.f;
+            bf16_t* orow = out + ((size_t)bb * N + i) * ((size_t)pb.H * DK) + (size_t)h * DK;
+#pragma unroll
+            for (int db = 0; db < NDB; ++db)
+#pragma unroll
+                for (int r4 = 0; r4 < 4; ++r4) {
+                    u32x2 w;
+                    w[0] = pack_bf16(r.O[db][4 * r4 + 0] * inv, r.O[db][4 * r4 + 1] * inv);
+                    w[1] = pack_bf16(r.O[db][4 * r4 + 2] * inv, r.O[db][4 * r4 + 3] * inv);
+                    *(u32x2*)(orow + 32 * db + 8 * r4 + 4 * g) = w;
+                }
+        }
+    }
+
+    // one atomic per wavefront
+#pragma unroll
+    for (int o = 32; o > 0; o >>= 1) cnt_logical += __shfl_xor(cnt_logical, o, 64);
+    if (lane == 0) {
+        count_add(pb.counters, (unsigned)work, cnt_logical, cnt_phys);
+    }
+}
+
+}  // namespace
+
+hipError_t launch_attn_pipe(const Problem& pb, const bf16_t* q, const bf16_t* k, const bf16_t* vt, bf16_t* out,
+                            int waves, hipStream_t s)
+{
+    const bool causal = pb.scheme == SCHEME_CAUSAL;
+    const int br = 32 * waves;
+    const int n_qtiles = (pb.N + br - 1) / br;
+    const int per_head = causal ? (n_qtiles + 1) / 2 : n_qtiles;
+    const int n_work = pb.B * pb.H * per_head;
+    const int grid = ((n_work + 7) / 8) * 8;
+    CountCfg cc;
+    cc.b = pb.b;
+    cc.b_shift = -1;
+    for (int sft = 0; sft < 31; ++sft)
+        if ((1 << sft) == pb.b) cc.b_shift = sft;
+#define ATTN_LAUNCH(DK_, W_, C_)                                                                                     \
+    hipLaunchKernelGGL((attn_pipe_kernel<DK_, W_, C_>), dim3(grid), dim3(64 * W_), 0, s, pb, cc, q, k, vt, out, \
+                       n_qtiles, per_head, n_work)
+    if (pb.d == 64 && waves == 4) { if (causal) ATTN_LAUNCH(64, 4, true); else ATTN_LAUNCH(64, 4, false); }
+    else if (pb.d == 64 && waves == 8) { if (causal) ATTN_LAUNCH(64, 8, true); else ATTN_LAUNCH(64, 8, false); }
+    else if (pb.d == 128 && waves == 8) { if (causal) ATTN_LAUNCH(128, 8, true); else ATTN_LAUNCH(128, 8, false); }
+    else return hipErrorInvalidValue;
+#undef ATTN_LAUNCH
+    return hipGetLastError();
+}
+
+}  // namespace attnring

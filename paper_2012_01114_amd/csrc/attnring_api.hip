@@ -79,9 +79,28 @@ Problem make_problem(const attn_ctx* c, int scheme)
     return pb;
 }
 
-__global__ void zero_counters_kernel(unsigned long long* c)
+__global__ __launch_bounds__(1024) void zero_counters_kernel(unsigned long long* c)
 {
-    if (threadIdx.x < CNT_WORDS) c[threadIdx.x] = 0ull;
+    for (int w = 0; w < CNT_WORDS; ++w) c[(size_t)threadIdx.x * CNT_SLOT_WORDS + w] = 0ull;  // CNT_SLOTS threads
+    if (threadIdx.x < CNT_WORDS) c[CNT_TOTALS + threadIdx.x] = 0ull;
+}
+
+// totals[w] = sum over the slots; one workgroup of CNT_SLOTS threads
+__global__ __launch_bounds__(1024) void sum_counters_kernel(unsigned long long* c)
+{
+    __shared__ unsigned long long part[CNT_WORDS][16];
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    for (int w = 0; w < CNT_WORDS; ++w) {
+        unsigned long long v = c[(size_t)threadIdx.x * CNT_SLOT_WORDS + w];
+        for (int o = 32; o > 0; o >>= 1) v += __shfl_xor(v, o, 64);
+        if (lane == 0) part[w][wave] = v;
+    }
+    __syncthreads();
+    if (threadIdx.x < CNT_WORDS) {
+        unsigned long long v = 0;
+        for (int i = 0; i < CNT_SLOTS / 64; ++i) v += part[threadIdx.x][i];
+        c[CNT_TOTALS + threadIdx.x] = v;
+    }
 }
 
 attn_status ensure_generic_workspace(attn_ctx* c)
@@ -159,8 +178,8 @@ attn_status attn_init(const attn_config* cfg, attn_ctx** out_ctx)
 
     c->mfma_shape = cfg->dtype == ATTN_BF16 && (cfg->d_k == 64 || cfg->d_k == 128) && cfg->d_model % 8 == 0 &&
                     c->scale > 0.f;
-    e = hipMalloc((void**)&c->counters, sizeof(unsigned long long) * CNT_WORDS);
-    if (e == hipSuccess) e = hipMemset(c->counters, 0, sizeof(unsigned long long) * CNT_WORDS);
+    e = hipMalloc((void**)&c->counters, sizeof(unsigned long long) * CNT_BUFFER_WORDS);
+    if (e == hipSuccess) e = hipMemset(c->counters, 0, sizeof(unsigned long long) * CNT_BUFFER_WORDS);
     if (e == hipSuccess && c->mfma_shape) {
         const size_t qkv = (size_t)cfg->batch * c->Npad * hd * sizeof(bf16_t);
         bf16_t** dst[3] = {&c->qb, &c->kb, &c->vtb};
@@ -238,7 +257,7 @@ attn_status attn_forward(attn_ctx* ctx, const void* X, const void* Wq, const voi
     if (e != hipSuccess) return hip_fail(ctx, what_, e);
 
     MARK(0);
-    hipLaunchKernelGGL(zero_counters_kernel, dim3(1), dim3(64), 0, s, ctx->counters);
+    hipLaunchKernelGGL(zero_counters_kernel, dim3(1), dim3(CNT_SLOTS), 0, s, ctx->counters);
     e = hipGetLastError();
     CHECK("launch zero_counters");
 
@@ -251,10 +270,10 @@ attn_status attn_forward(attn_ctx* ctx, const void* X, const void* Wq, const voi
         e = launch_proj_mfma(pb, (const bf16_t*)X, ctx->wt, ctx->qb, ctx->kb, ctx->vtb, s);
         CHECK("launch proj_mfma");
         MARK(2);
-        // The 256-row alternating-phase kernel is chosen by flag only.
-        const bool wide = (cf.flags & ATTN_FLAG_WIDE_TILES) != 0;
-        if (wide) e = launch_attn_pingpong(pb, ctx->qb, ctx->kb, ctx->vtb, (bf16_t*)out, s);
-        else e = launch_attn_mfma(pb, ctx->qb, ctx->kb, ctx->vtb, (bf16_t*)out, s);
+        // d_k = 64: 128-row workgroups of 4 wavefronts, three of them per CU; d_k = 128: 256 rows, 8 wavefronts
+        int waves = cf.d_k == 128 ? 8 : 4;
+        if (cf.d_k == 64 && (cf.flags & ATTN_FLAG_WIDE_TILES)) waves = 8;
+        e = launch_attn_pipe(pb, ctx->qb, ctx->kb, ctx->vtb, (bf16_t*)out, waves, s);
         CHECK("launch attention (mfma)");
         MARK(3);
         ctx->last_proj_gemms = 3;
@@ -305,10 +324,13 @@ attn_status attn_stats(attn_ctx* ctx, attn_stats_t* out)
     if (!ctx) return fail(nullptr, ATTN_ERR_INVALID, "attn_stats: NULL context%s");
     if (!out) return fail(ctx, ATTN_ERR_INVALID, "attn_stats: NULL output%s");
     if (!ctx->have_forward) return fail(ctx, ATTN_ERR_INVALID, "attn_stats: no attn_forward has run%s");
-    hipError_t e = hipStreamSynchronize(ctx->last_stream);
+    hipLaunchKernelGGL(sum_counters_kernel, dim3(1), dim3(CNT_SLOTS), 0, ctx->last_stream, ctx->counters);
+    hipError_t e = hipGetLastError();
+    if (e != hipSuccess) return hip_fail(ctx, "launch sum_counters", e);
+    e = hipStreamSynchronize(ctx->last_stream);
     if (e != hipSuccess) return hip_fail(ctx, "hipStreamSynchronize", e);
     unsigned long long cnt[CNT_WORDS];
-    e = hipMemcpy(cnt, ctx->counters, sizeof(cnt), hipMemcpyDeviceToHost);
+    e = hipMemcpy(cnt, ctx->counters + CNT_TOTALS, sizeof(cnt), hipMemcpyDeviceToHost);
     if (e != hipSuccess) return hip_fail(ctx, "hipMemcpy(counters)", e);
 
     const attn_config& cf = ctx->cfg;

@@ -21,11 +21,23 @@ struct Problem {
     bool noskip;         // debug: visit every tile, mask with -inf
     bool is_bf16;        // storage type of X, W, out
     const int* lens;     // device, [B] or nullptr
-    unsigned long long* counters;  // device: [0] logical tiles, [1] physical score blocks
+    unsigned long long* counters;  // device: CNT_SLOTS slots of (logical tiles, physical score blocks), then totals
 };
 
-// Device counters written by the attention kernels.
+// Device counters written by the attention kernels.  Adds to one address from thousands of
+// wavefronts serialise in L2, so the kernels add into one of CNT_SLOTS slots, each on a cache
+// line of its own, chosen by work item; a one-workgroup kernel sums the slots into the totals
+// (the two words that follow the slots) when the counts are asked for.
 enum { CNT_LOGICAL = 0, CNT_PHYS = 1, CNT_WORDS = 2 };
+enum { CNT_SLOTS = 1024, CNT_SLOT_WORDS = 16, CNT_TOTALS = CNT_SLOTS * CNT_SLOT_WORDS,
+       CNT_BUFFER_WORDS = CNT_TOTALS + CNT_WORDS };
+__device__ __forceinline__ void count_add(unsigned long long* counters, unsigned item, unsigned long long logical,
+                                          unsigned long long phys)
+{
+    unsigned long long* slot = counters + (size_t)(item & (CNT_SLOTS - 1)) * CNT_SLOT_WORDS;
+    if (logical) atomicAdd(&slot[CNT_LOGICAL], logical);
+    if (phys) atomicAdd(&slot[CNT_PHYS], phys);
+}
 
 // ---- generic float-compute path (any shape, f32 or bf16 storage) ----------
 // q/k/v workspace: float [B][H][N][d].
@@ -42,12 +54,10 @@ hipError_t launch_transpose_w(const Problem& pb, const bf16_t* Wq, const bf16_t*
                               bf16_t* Wt, hipStream_t s);
 hipError_t launch_proj_mfma(const Problem& pb, const bf16_t* X, const bf16_t* Wt, bf16_t* q, bf16_t* k,
                             bf16_t* vt, hipStream_t s);
-hipError_t launch_attn_mfma(const Problem& pb, const bf16_t* q, const bf16_t* k, const bf16_t* vt,
-                            bf16_t* out, hipStream_t s);
-// Same computation for long sequences: 256-row workgroups whose two wavefront groups
-// alternate between the softmax and the MFMA phases.
-hipError_t launch_attn_pingpong(const Problem& pb, const bf16_t* q, const bf16_t* k, const bf16_t* vt,
-                                bf16_t* out, hipStream_t s);
+// Fused phases 1-3 with redundant blocks left out; `waves` wavefronts of 32 rows per workgroup:
+// 4 or 8 for d_k = 64, 8 for d_k = 128.
+hipError_t launch_attn_pipe(const Problem& pb, const bf16_t* q, const bf16_t* k, const bf16_t* vt,
+                            bf16_t* out, int waves, hipStream_t s);
 // Physical score-block edge of the MFMA attention kernels (phys_br = phys_bc).
 enum { MFMA_BLOCK = 32 };
 

@@ -187,8 +187,7 @@ __global__ __launch_bounds__(256) void attn_generic_kernel(Problem pb, const flo
             int J = I - t; if (J < 0) J += P;
             if (pb.noskip || tile_needed(pb.scheme, I, J, b, len)) ++tiles;
         }
-        atomicAdd(&pb.counters[CNT_LOGICAL], tiles);
-        atomicAdd(&pb.counters[CNT_PHYS], tiles);
+        count_add(pb.counters, (blockIdx.z * gridDim.y + blockIdx.y) * gridDim.x + blockIdx.x, tiles, tiles);
     }
 
     for (int r = wave; r < b; r += 4) {
@@ -249,8 +248,8 @@ __global__ __launch_bounds__(256) void sym_scores_kernel(Problem pb, const float
         }
     }
     if (threadIdx.x == 0) {
-        atomicAdd(&pb.counters[CNT_LOGICAL], (unsigned long long)(gmax + 1));
-        atomicAdd(&pb.counters[CNT_PHYS], (unsigned long long)(gmax + 1));
+        count_add(pb.counters, (blockIdx.z * gridDim.y + blockIdx.y) * gridDim.x + blockIdx.x,
+                  (unsigned long long)(gmax + 1), (unsigned long long)(gmax + 1));
     }
 }
 

@@ -72,7 +72,7 @@ __global__ __launch_bounds__(256) void proj_mfma_kernel(int Bsz, int N, int Npad
                                                         const bf16_t* __restrict__ X,
                                                         const bf16_t* __restrict__ Wt, bf16_t* __restrict__ qo,
                                                         bf16_t* __restrict__ ko, bf16_t* __restrict__ vto,
-                                                        int tiles_x, int tiles_w)
+                                                        int tiles_x, int tiles_w, float qscale)
 {
     constexpr int WT = BT / 2;          // wavefront tile edge
     constexpr int NB = WT / 32;         // MFMA blocks per edge
@@ -184,9 +184,10 @@ __global__ __launch_bounds__(256) void proj_mfma_kernel(int Bsz, int N, int Npad
                     const int cc = col - which * HD;
                     const int h = cc / d, l = cc - h * d;
                     bf16_t* dst = (which ? ko : qo) + (((size_t)bb * H + h) * Npad + i) * d + l;
+                    const float qs = which ? 1.f : qscale;  // q is stored pre-multiplied (see launch_proj_mfma)
                     u32x2 w;
-                    w[0] = pack_bf16(acc[a][b][4 * r4 + 0], acc[a][b][4 * r4 + 1]);
-                    w[1] = pack_bf16(acc[a][b][4 * r4 + 2], acc[a][b][4 * r4 + 3]);
+                    w[0] = pack_bf16(acc[a][b][4 * r4 + 0] * qs, acc[a][b][4 * r4 + 1] * qs);
+                    w[1] = pack_bf16(acc[a][b][4 * r4 + 2] * qs, acc[a][b][4 * r4 + 3] * qs);
                     *(u32x2*)dst = w;
                 }
         }
@@ -229,7 +230,7 @@ template <int BT, int WR, int WC>
 __global__ __launch_bounds__(64 * WR * WC, (WR * WC) / 4 * (BT == 256 ? 1 : 2))
 void proj_dma_kernel(int Bsz, int N, int Npad, int D, int H, int d, const bf16_t* __restrict__ X,
                      const bf16_t* __restrict__ Wt, bf16_t* __restrict__ qo, bf16_t* __restrict__ ko,
-                     bf16_t* __restrict__ vto, int tiles_x, int tiles_w)
+                     bf16_t* __restrict__ vto, int tiles_x, int tiles_w, float qscale)
 {
     constexpr int NW = WR * WC;
     constexpr int TA = BT / WR, TB = BT / WC;    // wavefront tile: TA rows of the A side, TB of the B side
@@ -373,9 +374,10 @@ void proj_dma_kernel(int Bsz, int N, int Npad, int D, int H, int d, const bf16_t
                     const int cc = col - which * HD;
                     const int h = cc / d, l = cc - h * d;
                     bf16_t* dst = (which ? ko : qo) + (((size_t)bb * H + h) * Npad + i) * d + l;
+                    const float qs = which ? 1.f : qscale;  // q is stored pre-multiplied (see launch_proj_mfma)
                     u32x2 w;
-                    w[0] = pack_bf16(acc[a][b][4 * r4 + 0], acc[a][b][4 * r4 + 1]);
-                    w[1] = pack_bf16(acc[a][b][4 * r4 + 2], acc[a][b][4 * r4 + 3]);
+                    w[0] = pack_bf16(acc[a][b][4 * r4 + 0] * qs, acc[a][b][4 * r4 + 1] * qs);
+                    w[1] = pack_bf16(acc[a][b][4 * r4 + 2] * qs, acc[a][b][4 * r4 + 3] * qs);
                     *(u32x2*)dst = w;
                 }
         }
@@ -404,15 +406,21 @@ void proj_dma_kernel(int Bsz, int N, int Npad, int D, int H, int d, const bf16_t
     }
 }
 
+// The stored q carries the score scale and the change to base-2 exponentials:
+// q' = q * scale * log2(e), applied to the fp32 accumulator before the one rounding to
+// bf16, so that the attention kernels get base-2 scores straight out of the MFMA.
+inline float q_prescale(const Problem& pb) { return pb.scale * 1.4426950408889634f; }
+
 template <int BT, int WR, int WC>
 hipError_t launch_dma(const Problem& pb, const bf16_t* X, const bf16_t* Wt, bf16_t* q, bf16_t* k, bf16_t* vt,
                       hipStream_t s)
 {
+    const float qscale = q_prescale(pb);
     const int tiles_x = pb.B * pb.Npad / BT;
     const int tiles_w = 3 * pb.H * pb.d / BT;
     const int grid = ((tiles_x * tiles_w + 7) / 8) * 8;
     hipLaunchKernelGGL((proj_dma_kernel<BT, WR, WC>), dim3(grid), dim3(64 * WR * WC), 0, s, pb.B, pb.N, pb.Npad, pb.D,
-                       pb.H, pb.d, X, Wt, q, k, vt, tiles_x, tiles_w);
+                       pb.H, pb.d, X, Wt, q, k, vt, tiles_x, tiles_w, qscale);
     return hipGetLastError();
 }
 
@@ -420,11 +428,12 @@ template <int BT>
 hipError_t launch_bt(const Problem& pb, const bf16_t* X, const bf16_t* Wt, bf16_t* q, bf16_t* k, bf16_t* vt,
                      hipStream_t s)
 {
+    const float qscale = q_prescale(pb);
     const int tiles_x = pb.B * pb.Npad / BT;
     const int tiles_w = 3 * pb.H * pb.d / BT;
     const int grid = ((tiles_x * tiles_w + 7) / 8) * 8;
     hipLaunchKernelGGL(proj_mfma_kernel<BT>, dim3(grid), dim3(256), 0, s, pb.B, pb.N, pb.Npad, pb.D, pb.H, pb.d, X, Wt,
-                       q, k, vt, tiles_x, tiles_w);
+                       q, k, vt, tiles_x, tiles_w, qscale);
     return hipGetLastError();
 }
 
