@@ -65,6 +65,9 @@ struct Pipe {
     // CU (three wavefronts per SIMD); otherwise four stages and two wavefronts per SIMD.
     static constexpr int STAGES = (DK == 64 && WAVES == 4) ? 3 : 4;
     static constexpr int OCC = (DK == 64 && WAVES == 4) ? 3 : 2;
+    // Fold the reference into the score accumulator (saves a subtraction per pair, costs 16 registers):
+    // pays where the vector ALUs are the busier unit per MFMA, d_k = 128.
+    static constexpr bool USE_CNEG = DK == 128;
 
     struct Row {
         f32x16 O[NDB];  // O^T, un-normalised
@@ -119,7 +122,7 @@ struct Pipe {
     // the row's reference, so the result is the exponent phase 2 needs.
     static __device__ __forceinline__ f32x16 scores(const Row& r, const Frags& fr, const u32x4 (&qf)[NKS])
     {
-        f32x16 S = mfma32(fr.kf[0], qf[0], r.Cneg);
+        f32x16 S = mfma32(fr.kf[0], qf[0], USE_CNEG ? r.Cneg : zero16());
 #pragma unroll
         for (int ks = 1; ks < NKS; ++ks) S = mfma32(fr.kf[ks], qf[ks], S);
         return S;
@@ -134,8 +137,9 @@ struct Pipe {
     }
 
     // A score beyond the slack (or the first finite score of a row): move the reference to the
-    // row's largest score and rescale what the row has accumulated.
-    static __device__ __forceinline__ void raise_reference(Row& r, float mxl)
+    // row's largest score and rescale what the row has accumulated.  Returns what the reference
+    // went up by; the scores at hand were computed against the old reference.
+    static __device__ __forceinline__ float raise_reference(Row& r, float mxl)
     {
         asm volatile("" ::: "memory");  // keeps this rare path a branch of its own
         const float mx = fmaxf(mxl, __shfl_xor(mxl, 32, 64));  // both halves of a row agree
@@ -150,15 +154,17 @@ struct Pipe {
         for (int db = 0; db < NDB; ++db)
 #pragma unroll
             for (int e = 0; e < 16; ++e) r.O[db][e] *= alpha;
+        if (USE_CNEG) {
 #pragma unroll
-        for (int e = 0; e < 16; ++e) {
-            r.S[e] -= delta;  // the block at hand was computed against the old reference
-            r.Cneg[e] = -r.mref;
+            for (int e = 0; e < 16; ++e) r.Cneg[e] = -r.mref;
         }
+        return delta;
     }
 
     // Phase 2 (Eq. (2)) of the block in r.S; the row sum is normalised at the very end.
-    static __device__ __forceinline__ void exponentials(Row& r)
+    // SHIFT: the scores still refer to a reference that was `delta` lower.
+    template <bool SHIFT>
+    static __device__ __forceinline__ void exponentials(Row& r, float delta)
     {
         typedef __bf16 bf16x2 __attribute__((ext_vector_type(2)));
         const unsigned ones = 0x3f803f80u;  // (1, 1) in bf16
@@ -167,8 +173,9 @@ struct Pipe {
         for (int hf = 0; hf < 2; ++hf)
 #pragma unroll
             for (int w = 0; w < 4; ++w) {
-                const float p0 = __builtin_amdgcn_exp2f(r.S[8 * hf + 2 * w]);
-                const float p1 = __builtin_amdgcn_exp2f(r.S[8 * hf + 2 * w + 1]);
+                const float s0 = r.S[8 * hf + 2 * w], s1 = r.S[8 * hf + 2 * w + 1];
+                const float p0 = __builtin_amdgcn_exp2f(SHIFT ? s0 - delta : s0);
+                const float p1 = __builtin_amdgcn_exp2f(SHIFT ? s1 - delta : s1);
                 const unsigned pk = pack_bf16(p0, p1);
                 r.P[hf][w] = pk;
                 // the row sum takes the rounded weights, the ones phase 3 multiplies with
@@ -367,19 +374,27 @@ void attn_pipe_kernel(Problem pb, CountCfg cc, const bf16_t* __restrict__ q, con
                 auto phase_e = [&](auto upper, bool masked, int J) {
                     constexpr int UPPER = decltype(upper)::value;
                     if (masked) T::mask_block(r.S, lim_base - (J * BC + 32 * UPPER));
-                    const float mxl = T::max16(r.S);
-                    if (__builtin_amdgcn_ballot_w64(mxl > r.thr) != 0ull) T::raise_reference(r, mxl);
+                    const float mxl = T::USE_CNEG ? T::max16(r.S) : T::max16(r.S) - r.mref;
+                    float delta = 0.f;
+                    const bool raised = __builtin_amdgcn_ballot_w64(mxl > r.thr) != 0ull;
+                    if (raised) delta = T::raise_reference(r, mxl);
                     // requests first: V^T of this block; K of the next block, which is the lower half of
                     // this tile or the upper half of the next tile
                     T::read_v(fr, lds + stg, voff[0] ^ (64 * UPPER), voff[1] ^ (64 * UPPER));
                     T::read_k(fr, UPPER ? lds + stg : lds + stg_n + 32 * T::KROWB, koff);
                     __builtin_amdgcn_sched_barrier(0);
-                    T::exponentials(r);
+                    if constexpr (!T::USE_CNEG) {
+                        T::template exponentials<true>(r, r.mref);
+                    } else {
+                        if (raised) T::template exponentials<true>(r, delta);
+                        else T::template exponentials<false>(r, 0.f);
+                    }
                 };
                 auto phase_m = [&]() {
                     __builtin_amdgcn_s_setprio(1);
+                    r.S = T::scores(r, fr, qf);  // first, so that E(n+1) finds them done; after the last
+                                                 // block: of stale keys, unused
                     T::weighted_sum(r, fr);
-                    r.S = T::scores(r, fr, qf);  // after the last block: of stale keys, unused
                     __builtin_amdgcn_s_setprio(0);
                 };
                 auto next_tile = [&]() {
