@@ -257,12 +257,14 @@ attn_status attn_forward(attn_ctx* ctx, const void* X, const void* Wq, const voi
     if (e != hipSuccess) return hip_fail(ctx, what_, e);
 
     MARK(0);
-    hipLaunchKernelGGL(zero_counters_kernel, dim3(1), dim3(CNT_SLOTS), 0, s, ctx->counters);
-    e = hipGetLastError();
-    CHECK("launch zero_counters");
 
     const bool use_mfma = ctx->mfma_shape && scheme != ATTN_SCHEME_SYMMETRIC && aligned_to(X, 16) &&
                           aligned_to(out, 8) && aligned_to(Wq, 2) && aligned_to(Wk, 2) && aligned_to(Wv, 2);
+    if (!use_mfma) {  // the matrix-core path clears the counters in its first kernel
+        hipLaunchKernelGGL(zero_counters_kernel, dim3(1), dim3(CNT_SLOTS), 0, s, ctx->counters);
+        e = hipGetLastError();
+        CHECK("launch zero_counters");
+    }
     if (use_mfma) {
         e = launch_transpose_w(pb, (const bf16_t*)Wq, (const bf16_t*)Wk, (const bf16_t*)Wv, ctx->wt, s);
         CHECK("launch transpose_w");

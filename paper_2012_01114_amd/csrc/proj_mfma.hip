@@ -14,13 +14,26 @@ namespace attnring {
 namespace {
 
 // ---------------------------------------------------------------------------
-// W^T: 64 x 64 tiles through LDS; grid (HD/64, ceil(D/64), 3).
+// W^T: 64 x 64 tiles through LDS; grid (HD/64, ceil(D/64), 3).  Workgroup
+// (0,0,0) also clears the counter slots of the call (every forward pass runs
+// this kernel first).
 // ---------------------------------------------------------------------------
+__device__ __forceinline__ void clear_counters(unsigned long long* counters)
+{
+    if (blockIdx.x == 0 && blockIdx.y == 0 && blockIdx.z == 0) {
+        for (int sl = threadIdx.x; sl < CNT_SLOTS; sl += blockDim.x)
+            for (int w = 0; w < CNT_WORDS; ++w) counters[(size_t)sl * CNT_SLOT_WORDS + w] = 0ull;
+        if (threadIdx.x < CNT_WORDS) counters[CNT_TOTALS + threadIdx.x] = 0ull;
+    }
+}
+
 __global__ __launch_bounds__(256) void transpose_w_kernel(int D, int HD, const bf16_t* __restrict__ Wq,
                                                           const bf16_t* __restrict__ Wk,
-                                                          const bf16_t* __restrict__ Wv, bf16_t* __restrict__ Wt)
+                                                          const bf16_t* __restrict__ Wv, bf16_t* __restrict__ Wt,
+                                                          unsigned long long* counters)
 {
     __shared__ bf16_t tile[64][64 + 2];
+    clear_counters(counters);
     const bf16_t* W = blockIdx.z == 0 ? Wq : (blockIdx.z == 1 ? Wk : Wv);
     bf16_t* dst = Wt + (size_t)blockIdx.z * HD * D;
     const int c0 = blockIdx.x * 64, r0 = blockIdx.y * 64;
@@ -33,6 +46,42 @@ __global__ __launch_bounds__(256) void transpose_w_kernel(int D, int HD, const b
     for (int c = ty; c < 64; c += 4) {
         const int gk = r0 + tx;
         if (gk < D) dst[(size_t)(c0 + c) * D + gk] = tile[tx][c];
+    }
+}
+
+// The same for 16-byte aligned weights (D is a multiple of 8): 16 bytes per lane in and out.
+__global__ __launch_bounds__(256) void transpose_w16_kernel(int D, int HD, const bf16_t* __restrict__ Wq,
+                                                            const bf16_t* __restrict__ Wk,
+                                                            const bf16_t* __restrict__ Wv, bf16_t* __restrict__ Wt,
+                                                            unsigned long long* counters)
+{
+    constexpr int PITCH = 64 + 8;  // elements; keeps 16-byte alignment of the rows
+    __shared__ __attribute__((aligned(16))) bf16_t tile[64 * PITCH];
+    clear_counters(counters);
+    const bf16_t* W = blockIdx.z == 0 ? Wq : (blockIdx.z == 1 ? Wk : Wv);
+    bf16_t* dst = Wt + (size_t)blockIdx.z * HD * D;
+    const int c0 = blockIdx.x * 64, r0 = blockIdx.y * 64;
+#pragma unroll
+    for (int u = 0; u < 2; ++u) {
+        const int c = threadIdx.x + 256 * u;
+        const int row = c >> 3, cc = c & 7;
+        u32x4 v = {0u, 0u, 0u, 0u};
+        if (r0 + row < D) v = *(const u32x4*)(W + (size_t)(r0 + row) * HD + c0 + 8 * cc);
+        *(u32x4*)(tile + row * PITCH + 8 * cc) = v;
+    }
+    __syncthreads();
+#pragma unroll
+    for (int u = 0; u < 2; ++u) {
+        const int c = threadIdx.x + 256 * u;
+        const int n = c >> 3, kc = c & 7;
+        if (r0 + 8 * kc >= D) continue;
+        u32x4 v;
+#pragma unroll
+        for (int j = 0; j < 4; ++j) {
+            const unsigned lo = tile[(8 * kc + 2 * j) * PITCH + n], hi = tile[(8 * kc + 2 * j + 1) * PITCH + n];
+            v[j] = lo | (hi << 16);
+        }
+        *(u32x4*)(dst + (size_t)(c0 + n) * D + r0 + 8 * kc) = v;
     }
 }
 
@@ -443,8 +492,14 @@ hipError_t launch_transpose_w(const Problem& pb, const bf16_t* Wq, const bf16_t*
                               hipStream_t s)
 {
     const int HD = pb.H * pb.d;
-    hipLaunchKernelGGL(transpose_w_kernel, dim3(HD / 64, (pb.D + 63) / 64, 3), dim3(256), 0, s, pb.D, HD, Wq, Wk, Wv,
-                       Wt);
+    const dim3 grid(HD / 64, (pb.D + 63) / 64, 3);
+    const bool aligned16 = ((reinterpret_cast<uintptr_t>(Wq) | reinterpret_cast<uintptr_t>(Wk) |
+                             reinterpret_cast<uintptr_t>(Wv) | reinterpret_cast<uintptr_t>(Wt)) & 15) == 0 &&
+                           pb.D % 8 == 0;
+    if (aligned16)
+        hipLaunchKernelGGL(transpose_w16_kernel, grid, dim3(256), 0, s, pb.D, HD, Wq, Wk, Wv, Wt, pb.counters);
+    else
+        hipLaunchKernelGGL(transpose_w_kernel, grid, dim3(256), 0, s, pb.D, HD, Wq, Wk, Wv, Wt, pb.counters);
     return hipGetLastError();
 }
 
@@ -452,7 +507,9 @@ hipError_t launch_proj_mfma(const Problem& pb, const bf16_t* X, const bf16_t* Wt
                             hipStream_t s)
 {
     // Largest square tile that divides the per-matrix column count (so a tile never
-    // mixes q, k and v columns) and still gives every CU a few tiles.
+    // mixes q, k and v columns) and still gives every CU a few tiles.  (A ring of four 32-deep
+    // LDS stages with requests three slices ahead was measured slower than two 64-deep stages:
+    // twice the barriers, and request latency is not what holds this kernel back.)
     const int HD = pb.H * pb.d;
     const long rows = (long)pb.B * pb.Npad;
     const bool big = HD % 256 == 0 && rows % 256 == 0 && (rows / 256) * (3L * HD / 256) >= 512;
@@ -460,7 +517,6 @@ hipError_t launch_proj_mfma(const Problem& pb, const bf16_t* X, const bf16_t* Wt
         if (big) return launch_dma<256, 2, 4>(pb, X, Wt, q, k, vt, s);
         if (HD % 128 == 0) return launch_dma<128, 2, 2>(pb, X, Wt, q, k, vt, s);
     }
-    if (big) return launch_bt<256>(pb, X, Wt, q, k, vt, s);
     if (HD % 128 == 0) return launch_bt<128>(pb, X, Wt, q, k, vt, s);
     return launch_bt<64>(pb, X, Wt, q, k, vt, s);
 }
