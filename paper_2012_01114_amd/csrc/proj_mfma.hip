@@ -407,50 +407,82 @@ void proj_dma_kernel(int Bsz, int N, int Npad, int D, int H, int d, const bf16_t
     }
 
     // Epilogue.  acc[a][b][r]: A-side row wr*TA + 32a + acc_row(r,g), B-side row wc*TB + 32b + ln.
+    // A lane owns 8-byte runs whose neighbours in memory sit in other lanes' later registers, so
+    // storing them directly would touch 64 cache lines per instruction.  The tile is staged in LDS
+    // (free by now) in the order of the output arrays and leaves in 16-byte pieces, a full KiB of
+    // consecutive addresses per wavefront and instruction.  Staged rows are XOR-swizzled by 16-byte
+    // chunk like the operand tiles, which keeps both the 8-byte writes and the 16-byte reads spread
+    // over the banks.
+    constexpr int NT = 64 * NW;
+    constexpr int UNITS = BT * BT / 8;  // 16-byte pieces of the tile
+    const int dsh = d == 128 ? 7 : 6;   // d is 64 or 128 on this path
+    const int bb = x0 / Npad;           // Npad is a multiple of BT: one batch element per tile
+    const int i0 = x0 - bb * Npad;
     if (!is_v) {
+        // q and k: [head][vector][d], a staged row is one vector's d values of one head.
+        const int which = w0 >= HD ? 1 : 0;
+        const float qs = which ? 1.f : qscale;  // q is stored pre-multiplied (see launch_proj_mfma)
+        const int cmask = (d >> 3) - 1, rowb = 2 * d;
 #pragma unroll
         for (int b = 0; b < NBK; ++b) {
-            const int xr = x0 + wc * TB + 32 * b + ln;
-            const int bb = xr / Npad;
-            const int i = xr - bb * Npad;
-            if (i >= N) continue;
+            const int v = wc * TB + 32 * b + ln;
 #pragma unroll
             for (int a = 0; a < NA; ++a)
 #pragma unroll
                 for (int r4 = 0; r4 < 4; ++r4) {
-                    const int col = w0 + wr * TA + 32 * a + 8 * r4 + 4 * g;
-                    const int which = col >= HD ? 1 : 0;
-                    const int cc = col - which * HD;
-                    const int h = cc / d, l = cc - h * d;
-                    bf16_t* dst = (which ? ko : qo) + (((size_t)bb * H + h) * Npad + i) * d + l;
-                    const float qs = which ? 1.f : qscale;  // q is stored pre-multiplied (see launch_proj_mfma)
+                    const int ct = wr * TA + 32 * a + 8 * r4;  // tile column of register 4*r4 in half 0
+                    const int hc = ct >> dsh, c = (ct & (d - 1)) >> 3;
                     u32x2 w;
                     w[0] = pack_bf16(acc[a][b][4 * r4 + 0] * qs, acc[a][b][4 * r4 + 1] * qs);
                     w[1] = pack_bf16(acc[a][b][4 * r4 + 2] * qs, acc[a][b][4 * r4 + 3] * qs);
-                    *(u32x2*)dst = w;
+                    *(u32x2*)(lds + (hc * BT + v) * rowb + ((c ^ (v & cmask)) << 4) + 8 * g) = w;
                 }
         }
+        __syncthreads();
+        bf16_t* base = (which ? ko : qo) + ((size_t)bb * H + ((w0 - which * HD) >> dsh)) * Npad * d;
+#pragma unroll 4
+        for (int e0 = tid; e0 < UNITS; e0 += NT) {
+            const int hv = e0 >> (dsh - 3);  // head-in-tile * BT + vector
+            const int c = e0 & cmask;
+            const int hc = hv / BT, v = hv - hc * BT;
+            if (i0 + v >= N) continue;  // rows past n stay zero
+            const u32x4 val = *(const u32x4*)(lds + hv * rowb + ((c ^ (v & cmask)) << 4));
+            *(u32x4*)(base + ((size_t)hc * Npad + i0 + v) * d + c * 8) = val;
+        }
     } else {
+        // v transposed: [head][64-key block][d][64 key slots], a staged row is the 64 slots of one
+        // column; vectors past n are staged as zeros.
 #pragma unroll
         for (int b = 0; b < NBK; ++b) {
-            const int cc = w0 - 2 * HD + wc * TB + 32 * b + ln;
-            const int h = cc / d, l = cc - h * d;
+            const int cl = wc * TB + 32 * b + ln;
+            const int hc = cl >> dsh, l = cl & (d - 1);
 #pragma unroll
             for (int a = 0; a < NA; ++a)
 #pragma unroll
                 for (int r4 = 0; r4 < 4; ++r4) {
-                    const int xr = x0 + wr * TA + 32 * a + 8 * r4 + 4 * g;
-                    const int bb = xr / Npad;
-                    const int i = xr - bb * Npad;
-                    if (i >= N) continue;
-                    const int blk = i >> 6, r64 = i & 63;
+                    const int vl = wr * TA + 32 * a + 8 * r4 + 4 * g;  // vector of register 4*r4
+                    const int vb = vl >> 6, r64 = vl & 63;
                     const int slot = (r64 & 48) | vt_slot16(r64 & 15);
-                    bf16_t* dst = vto + ((((size_t)bb * H + h) * (Npad >> 6) + blk) * d + l) * 64 + slot;
+                    const int left = N - (i0 + vl);
                     u32x2 w;
-                    w[0] = pack_bf16(acc[a][b][4 * r4 + 0], acc[a][b][4 * r4 + 1]);
-                    w[1] = pack_bf16(acc[a][b][4 * r4 + 2], acc[a][b][4 * r4 + 3]);
-                    *(u32x2*)dst = w;
+                    w[0] = pack_bf16(left > 0 ? acc[a][b][4 * r4 + 0] : 0.f, left > 1 ? acc[a][b][4 * r4 + 1] : 0.f);
+                    w[1] = pack_bf16(left > 2 ? acc[a][b][4 * r4 + 2] : 0.f, left > 3 ? acc[a][b][4 * r4 + 3] : 0.f);
+                    *(u32x2*)(lds + ((hc * (BT / 64) + vb) * d + l) * 128 + (((slot >> 3) ^ (l & 7)) << 4) +
+                              2 * (slot & 7)) = w;
                 }
+        }
+        __syncthreads();
+        const int h0 = (w0 - 2 * HD) >> dsh;
+#pragma unroll 4
+        for (int e0 = tid; e0 < UNITS; e0 += NT) {
+            const int ul = e0 >> 3;  // (head-in-tile * blocks + block) * d + column
+            const int c = e0 & 7;
+            const int u = ul >> dsh, l = ul & (d - 1);
+            const int hc = u / (BT / 64), vb = u - hc * (BT / 64);
+            const int blk = (i0 >> 6) + vb;
+            if (blk * 64 >= N) continue;  // blocks past n stay zero
+            const u32x4 val = *(const u32x4*)(lds + ul * 128 + ((c ^ (l & 7)) << 4));
+            *(u32x4*)(vto + ((((size_t)bb * H + h0 + hc) * (Npad >> 6) + blk) * d + l) * 64 + c * 8) = val;
         }
     }
 }
