@@ -353,58 +353,68 @@ void proj_dma_kernel(int Bsz, int N, int Npad, int D, int H, int d, const bf16_t
 #pragma unroll
             for (int r = 0; r < 16; ++r) acc[a][b][r] = 0.f;
 
-    auto compute = [&](const int (&ao)[4], const int (&bo)[4]) {
-        u32x4 af[2][NA], bf[2][NBK];
+    // One k-step = the MFMAs of 16 k values on fragments that are already in registers, with the
+    // reads of the following k-step's fragments (order a0, b0.., a1..: what the first MFMAs need
+    // comes first) going out two at a time behind the first MFMAs.
+    u32x4 af[2][NA], bf[2][NBK];
+    auto load_frags = [&](u32x4 (&fa)[NA], u32x4 (&fb)[NBK], int ao, int bo) {
+        fa[0] = *(const u32x4*)(lds + ao);
 #pragma unroll
-        for (int a = 0; a < NA; ++a) af[0][a] = *(const u32x4*)(lds + ao[0] + a * 4096);
+        for (int b = 0; b < NBK; ++b) fb[b] = *(const u32x4*)(lds + bo + b * 4096);
 #pragma unroll
-        for (int b = 0; b < NBK; ++b) bf[0][b] = *(const u32x4*)(lds + bo[0] + b * 4096);
+        for (int a = 1; a < NA; ++a) fa[a] = *(const u32x4*)(lds + ao + a * 4096);
+    };
+    auto kstep = [&](const u32x4 (&fa)[NA], const u32x4 (&fb)[NBK]) {
 #pragma unroll
-        for (int ks = 0; ks < 4; ++ks) {
-            const int cur = ks & 1, nxt = cur ^ 1;
-            if (ks < 3) {
+        for (int a = 0; a < NA; ++a)
 #pragma unroll
-                for (int a = 0; a < NA; ++a) af[nxt][a] = *(const u32x4*)(lds + ao[ks + 1] + a * 4096);
-#pragma unroll
-                for (int b = 0; b < NBK; ++b) bf[nxt][b] = *(const u32x4*)(lds + bo[ks + 1] + b * 4096);
-            }
-#pragma unroll
-            for (int a = 0; a < NA; ++a)
-#pragma unroll
-                for (int b = 0; b < NBK; ++b) acc[a][b] = mfma32(af[cur][a], bf[cur][b], acc[a][b]);
-        }
-        // Issue order: the fragment reads of k-step ks+1 are spread between the MFMAs of k-step ks.
+            for (int b = 0; b < NBK; ++b) acc[a][b] = mfma32(fa[a], fb[b], acc[a][b]);
         constexpr int NRD = NA + NBK, NMF = NA * NBK;
-        __builtin_amdgcn_sched_group_barrier(0x100, NRD, 0);
+        static_assert(NRD % 2 == 0 && NRD / 2 <= NMF, "read pairs fit behind the MFMAs of a k-step");
 #pragma unroll
-        for (int ks = 0; ks < 3; ++ks) {
-#pragma unroll
-            for (int r = 0; r < NRD; ++r) {
-                __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
-                __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);
-            }
-            __builtin_amdgcn_sched_group_barrier(0x008, NMF - NRD, 0);
+        for (int r = 0; r < NRD / 2; ++r) {
+            __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
+            __builtin_amdgcn_sched_group_barrier(0x100, 2, 0);
         }
-        __builtin_amdgcn_sched_group_barrier(0x008, NMF, 0);
+        __builtin_amdgcn_sched_group_barrier(0x008, NMF - NRD / 2, 0);
+    };
+    // One 64-deep slice out of stage st.  Its first fragments are in af[0]/bf[0] on entry.  The
+    // one barrier of the slice sits before the last k-step, whose fragments are in registers by
+    // then: behind it the stage is free for the slice after next, the next slice (requested one
+    // slice ago) has landed, and its first fragments are read while the last MFMAs run, so the
+    // matrix pipe has work on both sides of the barrier.
+    auto slice = [&](const int (&ao)[4], const int (&bo)[4], int ao_next, int bo_next, bool more, int k_more,
+                     int st) {
+        load_frags(af[1], bf[1], ao[1], bo[1]);
+        kstep(af[0], bf[0]);
+        load_frags(af[0], bf[0], ao[2], bo[2]);
+        kstep(af[1], bf[1]);
+        load_frags(af[1], bf[1], ao[3], bo[3]);
+        kstep(af[0], bf[0]);
+        __builtin_amdgcn_sched_barrier(0);
+        __builtin_amdgcn_s_waitcnt(0x0070);  // vmcnt(0) lgkmcnt(0)
+        __builtin_amdgcn_s_barrier();
+        __builtin_amdgcn_sched_barrier(0);
+        if (more) issue(k_more, st);
+        load_frags(af[0], bf[0], ao_next, bo_next);
+        kstep(af[1], bf[1]);
     };
 
     const int nk = D / 64;
     issue(0, 0);
-    __builtin_amdgcn_s_waitcnt(0x0F70);  // vmcnt(0)
-    __syncthreads();
+    if (nk > 1) issue(64, 1);
+    if (nk > 1)
+        __builtin_amdgcn_s_waitcnt(0x0F70 | (2 * PPW));  // loads return in order: slice 0 has landed
+    else
+        __builtin_amdgcn_s_waitcnt(0x0F70);
+    __builtin_amdgcn_s_barrier();
+    load_frags(af[0], bf[0], aoff[0][0], boff[0][0]);
 #pragma nounroll
     for (int it = 0; it < nk; it += 2) {
-        if (it + 1 < nk) issue((it + 1) * 64, 1);
-        compute(aoff[0], boff[0]);
-        __builtin_amdgcn_s_waitcnt(0x0F70);
-        __syncthreads();
-        if (it + 1 < nk) {
-            if (it + 2 < nk) issue((it + 2) * 64, 0);
-            compute(aoff[1], boff[1]);
-            __builtin_amdgcn_s_waitcnt(0x0F70);
-            __syncthreads();
-        }
+        slice(aoff[0], boff[0], aoff[1][0], boff[1][0], it + 2 < nk, (it + 2) * 64, 0);
+        if (it + 1 < nk) slice(aoff[1], boff[1], aoff[0][0], boff[0][0], it + 3 < nk, (it + 3) * 64, 1);
     }
+    __syncthreads();  // the fragments read ahead for a slice that does not exist are dropped here
 
     // Epilogue.  acc[a][b][r]: A-side row wr*TA + 32a + acc_row(r,g), B-side row wc*TB + 32b + ln.
     // A lane owns 8-byte runs whose neighbours in memory sit in other lanes' later registers, so
