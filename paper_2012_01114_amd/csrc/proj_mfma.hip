@@ -267,13 +267,18 @@ __global__ __launch_bounds__(256) void proj_mfma_kernel(int Bsz, int N, int Npad
 }
 
 // ---------------------------------------------------------------------------
-// The same GEMM for d_model a multiple of 64, with the k slices copied from
-// global memory straight into LDS (global_load_lds, 16 bytes per lane).  LDS
-// rows are 128 bytes (64 bf16), unpadded; the eight 16-byte chunks of a row are
-// XOR-swizzled with bits 1..3 of the row index, which makes the 128-bit operand
-// reads of 16 consecutive rows conflict-free.  WR x WC wavefronts share a
-// BT x BT tile; fragments of the next k-step are read while the MFMAs of the
-// current one run.
+// The same GEMM for d_model a multiple of 64, with the operands copied from
+// global memory straight into LDS (global_load_lds, 16 bytes per lane).
+//
+// A request for 64 KiB of operands takes longer to come back than the MFMAs of one
+// 64-deep slice take to run, so two slices have to be in flight.  LDS cannot hold
+// three 64-deep stages of a 256 x 256 tile; it holds five 32-deep ones.  They form a
+// ring of slots; a slice is requested as two half slices into the two slots that the
+// half slices four and five behind it have left, which gives a request one and a half
+// slice periods to land.  A slot row is 64 bytes (32 bf16); its four 16-byte chunks
+// are XOR-swizzled with bits 2..3 of the row index, which keeps the 128-bit operand
+// reads of 16 consecutive rows on distinct banks.  WR x WC wavefronts share a BT x BT
+// tile.
 // ---------------------------------------------------------------------------
 template <int BT, int WR, int WC>
 __global__ __launch_bounds__(64 * WR * WC, (WR * WC) / 4 * (BT == 256 ? 1 : 2))
@@ -284,10 +289,13 @@ void proj_dma_kernel(int Bsz, int N, int Npad, int D, int H, int d, const bf16_t
     constexpr int NW = WR * WC;
     constexpr int TA = BT / WR, TB = BT / WC;    // wavefront tile: TA rows of the A side, TB of the B side
     constexpr int NA = TA / 32, NBK = TB / 32;   // MFMA blocks per edge
-    constexpr int SIDE = BT * 128;               // bytes of one operand side per stage
-    constexpr int STAGE = 2 * SIDE;
-    constexpr int PPW = (BT / 8) / NW;           // 1 KiB pieces (8 rows) per wavefront and side
-    __shared__ __attribute__((aligned(1024))) unsigned char lds[2 * STAGE];
+    constexpr int SIDE = BT * 64;                // bytes of one operand side per slot
+    constexpr int SLOT = 2 * SIDE;
+    constexpr int NSLOT = 5;
+    constexpr int PPW = (BT / 16) / NW;          // 1 KiB pieces (16 rows) per wavefront, side and slot
+    constexpr int PER_SLICE = 4 * PPW;           // requests of one wavefront per 64-deep slice
+    static_assert(PPW >= 1 && PER_SLICE <= 15, "piece count fits the wavefront count and the vmcnt field");
+    __shared__ __attribute__((aligned(1024))) unsigned char lds[NSLOT * SLOT];
 
     const int tid = threadIdx.x;
     const int lane = tid & 63, ln = lane & 31, g = lane >> 5;
@@ -304,46 +312,47 @@ void proj_dma_kernel(int Bsz, int N, int Npad, int D, int H, int d, const bf16_t
     const int x0 = tx_ * BT, w0 = tw * BT;
     const bool is_v = w0 >= 2 * HD;
 
-    // Source element offsets of this lane for its pieces (piece m = wave + NW*u holds rows 8m..8m+7;
-    // the lane lands at row 8m + lane/8, chunk position lane%8, and fetches the chunk that the
-    // swizzle puts there).
+    // Source byte offsets of this lane for its pieces (piece m = wave + NW*u holds rows
+    // 16m..16m+15; the lane lands at row 16m + lane/4, chunk position lane%4, and fetches the chunk
+    // that the swizzle puts there).  32 bits hold them (attn_init bounds the element counts), which
+    // lets a request take a uniform 64-bit base and this offset with no address arithmetic per lane.
     unsigned xoff[PPW], woff[PPW];
 #pragma unroll
     for (int u = 0; u < PPW; ++u) {
-        const int row = (wave + NW * u) * 8 + (lane >> 3);
-        const int c = (lane & 7) ^ ((row >> 1) & 7);
+        const int row = (wave + NW * u) * 16 + (lane >> 2);
+        const int c = (lane & 3) ^ ((row >> 2) & 3);
         const int xr = x0 + row;
         const int bb = xr / Npad;
         int i = xr - bb * Npad;
         i = i < N ? i : N - 1;
-        xoff[u] = (unsigned)(bb * N + i) * (unsigned)D + c * 8;
-        woff[u] = (unsigned)(w0 + row) * (unsigned)D + c * 8;
+        xoff[u] = 2u * ((unsigned)(bb * N + i) * (unsigned)D + c * 8);
+        woff[u] = 2u * ((unsigned)(w0 + row) * (unsigned)D + c * 8);
     }
     const int x_side = is_v ? 0 : SIDE, w_side = is_v ? SIDE : 0;
-    auto issue = [&](int k0, int stage) {
-        unsigned char* base = lds + stage * STAGE;
+    // Request number q (0 .. PER_SLICE-1) of the slice that starts at k0: piece u = q/4, operand
+    // q/2%2, half q%2 (the two halves of a row share a cache line and are requested back to back).
+    // The first half of the slice goes into slot s0, the second into slot s1.
+    auto request = [&](int q, int k0, int s0, int s1) {
+        const int u = q >> 2, w_op = (q >> 1) & 1, h = q & 1;
+        const int m = wave + NW * u;
+        unsigned char* dst = lds + (h ? s1 : s0) * SLOT + m * 1024 + (w_op ? w_side : x_side);
+        const char* src = (const char*)((w_op ? Wt : X) + k0 + 32 * h) + (w_op ? woff[u] : xoff[u]);
+        __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void*)src,
+                                         (__attribute__((address_space(3))) void*)dst, 16, 0, 0);
+    };
+    auto issue = [&](int k0, int s0, int s1) {
 #pragma unroll
-        for (int u = 0; u < PPW; ++u) {
-            const int m = wave + NW * u;
-            __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void*)(X + (size_t)xoff[u] + k0),
-                                             (__attribute__((address_space(3))) void*)(base + x_side + m * 1024), 16,
-                                             0, 0);
-            __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void*)(Wt + (size_t)woff[u] + k0),
-                                             (__attribute__((address_space(3))) void*)(base + w_side + m * 1024), 16,
-                                             0, 0);
-        }
+        for (int q = 0; q < PER_SLICE; ++q) request(q, k0, s0, s1);
     };
 
-    // LDS byte offsets of this lane's operand reads for the four k-steps of a slice, both stages.
-    int aoff[2][4], boff[2][4];
+    // LDS byte offsets of this lane's operand reads for the two k-steps of a slot, from the slot base.
+    int aoff[2], boff[2];
 #pragma unroll
-    for (int st = 0; st < 2; ++st)
-#pragma unroll
-        for (int ks = 0; ks < 4; ++ks) {
-            const int sw = ((2 * ks + g) ^ ((ln >> 1) & 7)) * 16;
-            aoff[st][ks] = st * STAGE + (wr * TA + ln) * 128 + sw;
-            boff[st][ks] = st * STAGE + SIDE + (wc * TB + ln) * 128 + sw;
-        }
+    for (int ks = 0; ks < 2; ++ks) {
+        const int sw = ((2 * ks + g) ^ ((ln >> 2) & 3)) * 16;
+        aoff[ks] = (wr * TA + ln) * 64 + sw;
+        boff[ks] = SIDE + (wc * TB + ln) * 64 + sw;
+    }
 
     f32x16 acc[NA][NBK];
 #pragma unroll
@@ -353,68 +362,90 @@ void proj_dma_kernel(int Bsz, int N, int Npad, int D, int H, int d, const bf16_t
 #pragma unroll
             for (int r = 0; r < 16; ++r) acc[a][b][r] = 0.f;
 
-    // One k-step = the MFMAs of 16 k values on fragments that are already in registers, with the
-    // reads of the following k-step's fragments (order a0, b0.., a1..: what the first MFMAs need
-    // comes first) going out two at a time behind the first MFMAs.
+    // One k-step = the MFMAs of 16 k values on fragments that are already in registers.  Behind
+    // the first MFMAs go, two at a time, the reads of the fragments of the following k-step (order
+    // a0, b0.., a1..: what its first MFMAs need comes first); nd requests (numbers q0 .. q0+nd-1 of
+    // a slice) are spread over the MFMAs: a wavefront that sends all requests of a slice in one run
+    // issues no MFMA meanwhile, and since all wavefronts do so at the same point the matrix pipe
+    // would drain.  The order is pinned with scheduling fences; the group-barrier solver drops its
+    // pattern as soon as memory requests are part of it.
     u32x4 af[2][NA], bf[2][NBK];
-    auto load_frags = [&](u32x4 (&fa)[NA], u32x4 (&fb)[NBK], int ao, int bo) {
-        fa[0] = *(const u32x4*)(lds + ao);
-#pragma unroll
-        for (int b = 0; b < NBK; ++b) fb[b] = *(const u32x4*)(lds + bo + b * 4096);
-#pragma unroll
-        for (int a = 1; a < NA; ++a) fa[a] = *(const u32x4*)(lds + ao + a * 4096);
+    auto read_frag = [&](u32x4 (&fa)[NA], u32x4 (&fb)[NBK], int r, const unsigned char* pa, const unsigned char* pb) {
+        if (r == 0) fa[0] = *(const u32x4*)pa;
+        else if (r <= NBK) fb[r - 1] = *(const u32x4*)(pb + (r - 1) * 2048);
+        else fa[r - NBK] = *(const u32x4*)(pa + (r - NBK) * 2048);
     };
-    auto kstep = [&](const u32x4 (&fa)[NA], const u32x4 (&fb)[NBK]) {
+    auto load_frags = [&](u32x4 (&fa)[NA], u32x4 (&fb)[NBK], int slot, int ks) {
+#pragma unroll
+        for (int r = 0; r < NA + NBK; ++r)
+            read_frag(fa, fb, r, lds + slot * SLOT + aoff[ks], lds + slot * SLOT + boff[ks]);
+    };
+    auto kstep = [&](const u32x4 (&fa)[NA], const u32x4 (&fb)[NBK], u32x4 (&na)[NA], u32x4 (&nb)[NBK], int slot,
+                     int ks, auto nd_, int q0, int k0, int s0, int s1) {
+        constexpr int ND = decltype(nd_)::value;
+        constexpr int NRD = NA + NBK, NMF = NA * NBK;
+        static_assert(NRD % 2 == 0 && NRD / 2 <= NMF, "read pairs fit behind the MFMAs of a k-step");
+        static_assert(ND <= NMF, "at most one request per MFMA");
+        const unsigned char* pa = lds + slot * SLOT + aoff[ks];
+        const unsigned char* pb = lds + slot * SLOT + boff[ks];
+        __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
         for (int a = 0; a < NA; ++a)
 #pragma unroll
-            for (int b = 0; b < NBK; ++b) acc[a][b] = mfma32(fa[a], fb[b], acc[a][b]);
-        constexpr int NRD = NA + NBK, NMF = NA * NBK;
-        static_assert(NRD % 2 == 0 && NRD / 2 <= NMF, "read pairs fit behind the MFMAs of a k-step");
-#pragma unroll
-        for (int r = 0; r < NRD / 2; ++r) {
-            __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
-            __builtin_amdgcn_sched_group_barrier(0x100, 2, 0);
-        }
-        __builtin_amdgcn_sched_group_barrier(0x008, NMF - NRD / 2, 0);
+            for (int b = 0; b < NBK; ++b) {
+                acc[a][b] = mfma32(fa[a], fb[b], acc[a][b]);
+                const int m = a * NBK + b + 1;  // MFMAs issued so far
+                if (m <= NRD / 2) {
+                    read_frag(na, nb, 2 * m - 2, pa, pb);
+                    read_frag(na, nb, 2 * m - 1, pa, pb);
+                }
+                if (ND > 0 && (m * ND) % NMF == 0) request(q0 + m * ND / NMF - 1, k0, s0, s1);
+                __builtin_amdgcn_sched_barrier(0);
+            }
     };
-    // One 64-deep slice out of stage st.  Its first fragments are in af[0]/bf[0] on entry.  The
-    // one barrier of the slice sits before the last k-step, whose fragments are in registers by
-    // then: behind it the stage is free for the slice after next, the next slice (requested one
-    // slice ago) has landed, and its first fragments are read while the last MFMAs run, so the
-    // matrix pipe has work on both sides of the barrier.
-    auto slice = [&](const int (&ao)[4], const int (&bo)[4], int ao_next, int bo_next, bool more, int k_more,
-                     int st) {
-        load_frags(af[1], bf[1], ao[1], bo[1]);
-        kstep(af[0], bf[0]);
-        load_frags(af[0], bf[0], ao[2], bo[2]);
-        kstep(af[1], bf[1]);
-        load_frags(af[1], bf[1], ao[3], bo[3]);
-        kstep(af[0], bf[0]);
-        __builtin_amdgcn_sched_barrier(0);
-        __builtin_amdgcn_s_waitcnt(0x0070);  // vmcnt(0) lgkmcnt(0)
+    auto next_slot = [](int s) { return s + 1 >= NSLOT ? s + 1 - NSLOT : s + 1; };
+    constexpr std::integral_constant<int, 0> no_req{};
+
+    // Slice j: half slices in slots sa and its successor.  The barrier of a half slice sits before
+    // its second k-step, whose fragments are in registers by then: behind it the slot is free, and
+    // the first fragments of the next half slice are read while the second k-step's MFMAs run, so
+    // the matrix pipe has work on both sides of the barrier.  With `more`, slice j+2 is requested
+    // behind the first barrier, into the slot that the half slice before this one left and into sa.
+    auto slice = [&](auto more_, int j, int sa) {
+        constexpr bool MORE = decltype(more_)::value;
+        constexpr std::integral_constant<int, MORE ? PER_SLICE / 2 : 0> nreq{};
+        const int sb = next_slot(sa), sc = next_slot(sb), se = next_slot(next_slot(sc));
+        const int k2 = (j + 2) * 64;
+        kstep(af[0], bf[0], af[1], bf[1], sa, 1, no_req, 0, 0, 0, 0);
+        __builtin_amdgcn_s_waitcnt(0xC07F);  // lgkmcnt(0)
         __builtin_amdgcn_s_barrier();
-        __builtin_amdgcn_sched_barrier(0);
-        if (more) issue(k_more, st);
-        load_frags(af[0], bf[0], ao_next, bo_next);
-        kstep(af[1], bf[1]);
+        kstep(af[1], bf[1], af[0], bf[0], sb, 0, nreq, 0, k2, se, sa);
+        kstep(af[0], bf[0], af[1], bf[1], sb, 1, nreq, PER_SLICE / 2, k2, se, sa);
+        // lgkmcnt(0); slice j+1 has landed (loads return in order; slice j+2 may be in flight)
+        __builtin_amdgcn_s_waitcnt(0x0070 | (MORE ? PER_SLICE : 0));
+        __builtin_amdgcn_s_barrier();
+        kstep(af[1], bf[1], af[0], bf[0], sc, 0, no_req, 0, 0, 0, 0);  // reads ahead into slice j+1
+        return sc;
     };
 
-    const int nk = D / 64;
-    issue(0, 0);
-    if (nk > 1) issue(64, 1);
-    if (nk > 1)
-        __builtin_amdgcn_s_waitcnt(0x0F70 | (2 * PPW));  // loads return in order: slice 0 has landed
-    else
+    const int ns = D / 64;
+    issue(0, 0, 1);
+    if (ns > 1) {
+        issue(64, 2, 3);
+        __builtin_amdgcn_s_waitcnt(0x0F70 | PER_SLICE);  // loads return in order: slice 0 has landed
+    } else {
         __builtin_amdgcn_s_waitcnt(0x0F70);
-    __builtin_amdgcn_s_barrier();
-    load_frags(af[0], bf[0], aoff[0][0], boff[0][0]);
-#pragma nounroll
-    for (int it = 0; it < nk; it += 2) {
-        slice(aoff[0], boff[0], aoff[1][0], boff[1][0], it + 2 < nk, (it + 2) * 64, 0);
-        if (it + 1 < nk) slice(aoff[1], boff[1], aoff[0][0], boff[0][0], it + 3 < nk, (it + 3) * 64, 1);
     }
-    __syncthreads();  // the fragments read ahead for a slice that does not exist are dropped here
+    __builtin_amdgcn_s_barrier();
+    load_frags(af[0], bf[0], 0, 0);
+    int sa = 0;  // slot of the first half of slice j
+    int j = 0;
+#pragma nounroll
+    for (; j + 2 < ns; ++j) sa = slice(std::true_type{}, j, sa);
+#pragma nounroll
+    for (; j < ns; ++j) sa = slice(std::false_type{}, j, sa);
+    __builtin_amdgcn_s_waitcnt(0x0070);  // the fragments read ahead for a slice that does not exist are dropped
+    __builtin_amdgcn_s_barrier();
 
     // Epilogue.  acc[a][b][r]: A-side row wr*TA + 32a + acc_row(r,g), B-side row wc*TB + 32b + ln.
     // A lane owns 8-byte runs whose neighbours in memory sit in other lanes' later registers, so
