@@ -433,11 +433,15 @@ void attn_pipe_kernel(Problem pb, CountCfg cc, const bf16_t* __restrict__ q, con
             __builtin_amdgcn_s_barrier();  // the next pass refills the stages
         }
 
-        // y_i = O_i / l_i ; a row with no allowed pair is zero.
-        const float l_tot = r.l + __shfl_xor(r.l, 32, 64);
-        if (i < N) {
+        // y_i = O_i / l_i ; a row with no allowed pair is zero.  A lane owns 8-byte runs of 32 rows,
+        // so the wavefront's 32 x d_k tile goes through LDS (the ring is idle between passes; rows
+        // swizzled by 16-byte chunk as everywhere) and leaves as whole 16-byte pieces, four or eight
+        // full rows per store instruction.
+        {
+            constexpr int CPR = DK / 8;  // 16-byte chunks per row
+            const float l_tot = r.l + __shfl_xor(r.l, 32, 64);
             const float inv = l_tot > 0.f ? 1.f / l_tot : 0.f;
-            bf16_t* orow = out + ((size_t)bb * N + i) * ((size_t)pb.H * DK) + (size_t)h * DK;
+            unsigned char* stage = lds + wave * (32 * DK * 2);
 #pragma unroll
             for (int db = 0; db < NDB; ++db)
 #pragma unroll
@@ -445,8 +449,22 @@ void attn_pipe_kernel(Problem pb, CountCfg cc, const bf16_t* __restrict__ q, con
                     u32x2 w;
                     w[0] = pack_bf16(r.O[db][4 * r4 + 0] * inv, r.O[db][4 * r4 + 1] * inv);
                     w[1] = pack_bf16(r.O[db][4 * r4 + 2] * inv, r.O[db][4 * r4 + 3] * inv);
-                    *(u32x2*)(orow + 32 * db + 8 * r4 + 4 * g) = w;
+                    const int c = 4 * db + r4;
+                    *(u32x2*)(stage + ln * (DK * 2) + ((c ^ (ln & (CPR - 1))) << 4) + 8 * g) = w;
                 }
+            __builtin_amdgcn_s_waitcnt(0xC07F);  // lgkmcnt(0): only this wavefront reads what it wrote
+            bf16_t* obase = out + ((size_t)bb * N + i0w) * ((size_t)pb.H * DK) + (size_t)h * DK;
+#pragma unroll
+            for (int it = 0; it < 32 * CPR / 64; ++it) {
+                const int row = it * (64 / CPR) + lane / CPR, c = lane % CPR;
+                const u32x4 v = *(const u32x4*)(stage + row * (DK * 2) + ((c ^ (row & (CPR - 1))) << 4));
+                if (i0w + row < N) *(u32x4*)(obase + (size_t)row * ((size_t)pb.H * DK) + c * 8) = v;
+            }
+            if (pass + 1 < n_pass) {
+                // the next pass refills the ring: every wavefront has to be done with its staging first
+                __builtin_amdgcn_s_waitcnt(0xC07F);
+                __builtin_amdgcn_s_barrier();
+            }
         }
     }
 
