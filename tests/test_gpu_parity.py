@@ -79,6 +79,8 @@ def test_symmetric_without_projection():
     (1, 136, 72, 1, 128, 17),     # d_model not a multiple of 64 (k tail)
     (1, 520, 64, 2, 64, 5),       # partitions larger than a score block (104 rows)
     (1, 1096, 64, 1, 128, 137),   # several 256-row tiles and a ragged tail
+    (1, 264, 192, 2, 64, 33),     # three 64-deep slices of d_model: the slice ring starts and ends at once
+    (2, 256, 320, 2, 128, 32),    # five slices: one steady turn of the slice ring, then its tail
 ])
 @pytest.mark.parametrize("scheme", [FULL, CAUSAL])
 @pytest.mark.parametrize("tiles", [ar.ATTN_FLAG_NARROW_TILES, ar.ATTN_FLAG_WIDE_TILES])
