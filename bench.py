@@ -156,7 +156,9 @@ def main():
     pairs = needed_pairs(w, lens)
     assert pairs == stats["pairs_needed"][0], (pairs, stats["pairs_needed"])
     attn_flop = 4.0 * w.d_k * pairs
-    proj_flop = 6.0 * w.batch * w.n * w.d_model * w.hd
+    # projection: every q row, and the k and v rows that some allowed pair uses (those below the key length)
+    kv_rows = w.batch * w.n if lens is None else int(np.minimum(np.maximum(lens, 0), w.n).sum())
+    proj_flop = 2.0 * (w.batch * w.n + 2 * kv_rows) * w.d_model * w.hd
     value = (attn_flop + proj_flop) / (ms_step * 1e-3) / 1e12
 
     kern = {

@@ -105,15 +105,43 @@ constexpr int ROWB = BK * 2 + 16;  // LDS bytes per tile row (padded)
 // ~32 tiles in flight on one XCD form a 4 x 8 patch that shares its operand
 // slices in that XCD's L2 instead of fetching 32 different x slices.
 constexpr int GROUP_W = 4;
-__device__ __forceinline__ void tile_of(int id, int tiles_x, int tiles_w, int& tw, int& tx)
+__device__ __forceinline__ void tile_of(int id, int tiles_x, int tiles_w, int& tw, int& tx, int group_w = GROUP_W)
 {
-    const int width = GROUP_W * tiles_x;
+    const int width = group_w * tiles_x;
     const int grp = id / width;
-    const int first_w = grp * GROUP_W;
-    const int gsz = min(tiles_w - first_w, GROUP_W);
+    const int first_w = grp * group_w;
+    const int gsz = min(tiles_w - first_w, group_w);
     const int local = id - grp * width;
     tx = local / gsz;
     tw = first_w + (local - tx * gsz);
+}
+// With key lengths some k and v tiles return at once, and an XCD keeps the run of tiles it was
+// given: the order above would hand some XCDs q tiles only and others the short batch items.
+// Both tile indices are therefore permuted, so that every run holds q, k and v tiles in equal
+// parts (groups of three column tiles, dealt round-robin over the three matrices) and x tiles
+// from all over the batch (a multiplier that is coprime to their number).
+__device__ __forceinline__ void spread_tiles(int tiles_x, int tiles_w, int& tw, int& tx)
+{
+    const int per_matrix = tiles_w / 3;
+    tw = (tw % 3) * per_matrix + tw / 3;
+    int mult = tiles_x / 8 + 1;
+    while (true) {  // the next number coprime to tiles_x
+        int a = mult, b = tiles_x;
+        while (b) { const int r = a % b; a = b; b = r; }
+        if (a == 1) break;
+        ++mult;
+    }
+    tx = (int)(((long long)tx * mult) % tiles_x);
+}
+
+// Whether every row of the x tile that starts at flattened row x0 (Npad rows per batch item, a
+// multiple of the tile height) lies at or past the key length of its batch item.
+__device__ __forceinline__ bool past_key_length(const int* __restrict__ lens, int x0, int Npad, int N)
+{
+    const int bb = x0 / Npad;
+    int len = lens[bb];
+    len = len < 0 ? 0 : (len > N ? N : len);
+    return x0 - bb * Npad >= len;
 }
 
 template <int BT>
@@ -121,7 +149,7 @@ __global__ __launch_bounds__(256) void proj_mfma_kernel(int Bsz, int N, int Npad
                                                         const bf16_t* __restrict__ X,
                                                         const bf16_t* __restrict__ Wt, bf16_t* __restrict__ qo,
                                                         bf16_t* __restrict__ ko, bf16_t* __restrict__ vto,
-                                                        int tiles_x, int tiles_w, float qscale)
+                                                        int tiles_x, int tiles_w, float qscale, const int* __restrict__ lens)
 {
     constexpr int WT = BT / 2;          // wavefront tile edge
     constexpr int NB = WT / 32;         // MFMA blocks per edge
@@ -144,6 +172,9 @@ __global__ __launch_bounds__(256) void proj_mfma_kernel(int Bsz, int N, int Npad
     const int x0 = tx_ * BT;   // first x-side row (padded vector index)
     const int w0 = tw * BT;    // first stacked output column
     const bool is_v = w0 >= 2 * HD;
+    // Keys past the key length of their batch item are in no allowed pair (Sec. 5.1 applied to
+    // padding): their k and v rows are not computed.  (q rows are: every query row has an output.)
+    if (lens != nullptr && w0 >= HD && past_key_length(lens, x0, Npad, N)) return;
 
     // per-thread source rows: chunk ch = tid + 256*u -> row ch/8, k-chunk ch%8
     const int kc = tid & 7;
@@ -284,7 +315,7 @@ template <int BT, int WR, int WC>
 __global__ __launch_bounds__(64 * WR * WC, (WR * WC) / 4 * (BT == 256 ? 1 : 2))
 void proj_dma_kernel(int Bsz, int N, int Npad, int D, int H, int d, const bf16_t* __restrict__ X,
                      const bf16_t* __restrict__ Wt, bf16_t* __restrict__ qo, bf16_t* __restrict__ ko,
-                     bf16_t* __restrict__ vto, int tiles_x, int tiles_w, float qscale)
+                     bf16_t* __restrict__ vto, int tiles_x, int tiles_w, float qscale, const int* __restrict__ lens)
 {
     constexpr int NW = WR * WC;
     constexpr int TA = BT / WR, TB = BT / WC;    // wavefront tile: TA rows of the A side, TB of the B side
@@ -308,9 +339,13 @@ void proj_dma_kernel(int Bsz, int N, int Npad, int D, int H, int d, const bf16_t
     const int tile_id = (blockIdx.x & 7) * per_xcd + (blockIdx.x >> 3);
     if (tile_id >= n_tiles) return;
     int tw, tx_;
-    tile_of(tile_id, tiles_x, tiles_w, tw, tx_);
+    tile_of(tile_id, tiles_x, tiles_w, tw, tx_, lens != nullptr ? 3 : GROUP_W);
+    if (lens != nullptr) spread_tiles(tiles_x, tiles_w, tw, tx_);
     const int x0 = tx_ * BT, w0 = tw * BT;
     const bool is_v = w0 >= 2 * HD;
+    // Keys past the key length of their batch item are in no allowed pair (Sec. 5.1 applied to
+    // padding): their k and v rows are not computed.  (q rows are: every query row has an output.)
+    if (lens != nullptr && w0 >= HD && past_key_length(lens, x0, Npad, N)) return;
 
     // Source byte offsets of this lane for its pieces (piece m = wave + NW*u holds rows
     // 16m..16m+15; the lane lands at row 16m + lane/4, chunk position lane%4, and fetches the chunk
@@ -542,7 +577,7 @@ hipError_t launch_dma(const Problem& pb, const bf16_t* X, const bf16_t* Wt, bf16
     const int tiles_w = 3 * pb.H * pb.d / BT;
     const int grid = ((tiles_x * tiles_w + 7) / 8) * 8;
     hipLaunchKernelGGL((proj_dma_kernel<BT, WR, WC>), dim3(grid), dim3(64 * WR * WC), 0, s, pb.B, pb.N, pb.Npad, pb.D,
-                       pb.H, pb.d, X, Wt, q, k, vt, tiles_x, tiles_w, qscale);
+                       pb.H, pb.d, X, Wt, q, k, vt, tiles_x, tiles_w, qscale, pb.noskip ? nullptr : pb.lens);
     return hipGetLastError();
 }
 
@@ -555,7 +590,7 @@ hipError_t launch_bt(const Problem& pb, const bf16_t* X, const bf16_t* Wt, bf16_
     const int tiles_w = 3 * pb.H * pb.d / BT;
     const int grid = ((tiles_x * tiles_w + 7) / 8) * 8;
     hipLaunchKernelGGL(proj_mfma_kernel<BT>, dim3(grid), dim3(256), 0, s, pb.B, pb.N, pb.Npad, pb.D, pb.H, pb.d, X, Wt,
-                       q, k, vt, tiles_x, tiles_w, qscale);
+                       q, k, vt, tiles_x, tiles_w, qscale, pb.noskip ? nullptr : pb.lens);
     return hipGetLastError();
 }
 

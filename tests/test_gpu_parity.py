@@ -148,6 +148,28 @@ def test_repeat_calls_are_stable():
     assert np.array_equal(a, b) and sa == sb
 
 
+@pytest.mark.parametrize("scheme", [FULL, CAUSAL])
+def test_key_lengths_change_between_calls(scheme):
+    """k and v rows past the key length are not projected; the workspace keeps whatever an earlier
+    call with longer keys left there, and none of it may reach a result."""
+    import torch
+    w = hp.custom_workload("lens_change", 3, 600, 128, 2, 64, 75, "bf16", scheme, 77)
+    stored, f64 = inputs.make_inputs(w)
+    stored["lens"] = np.array([600, 600, 517], dtype=np.int32)
+    run = hp.GpuRun(w, stored)
+    try:
+        for lens in (stored["lens"], np.array([100, 300, 0], dtype=np.int32),
+                     np.array([257, 64, 600], dtype=np.int32)):
+            print(f"[lens] {lens.tolist()}", flush=True)
+            dev_lens = torch.from_numpy(lens).to(run.X.device)
+            ar.attn_set_key_lengths(run.ctx, dev_lens)
+            got, stats = run.forward(scheme)
+            hp.tol_check(got, hp.oracle_forward(w, f64, scheme, 0.0, lens=lens), w.dtype)
+            hp.check_counts(stats, hp.oracle_counts(w, scheme, lens))
+    finally:
+        run.close()
+
+
 # ---- workloads 4 and 5: sampled rows + counts + a property that holds at any size --------------
 def _sampled_rows(w, lens, picks):
     stored, f64 = inputs.make_inputs(w)
