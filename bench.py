@@ -4,8 +4,9 @@ One step = one attn_forward: weight re-layout, q/k/v projection GEMM and the
 fused score/softmax/weighted-sum kernel with redundancy skipping, on synthetic
 inputs already resident in HBM.  Prints ONE JSON line.
 
-  value     useful TFLOP/s of the whole call: (projection FLOPs + 4*d_k FLOPs per
-            NEEDED pair, i.e. post-skip) / wall time per step
+  value     useful TFLOP/s of the whole call: (projection FLOPs of the rows some
+            allowed pair uses + 4*d_k FLOPs per NEEDED pair, i.e. post-skip) /
+            wall time per step
   roofline  the dominant kernel (by time) against the bf16 MFMA peak; its
             duration is measured with HIP events recorded by the library on the
             launch stream around every kernel of the timed steps
