@@ -24,6 +24,10 @@
  *   - the row maximum is subtracted before exp (same value, no overflow);
  *   - key lengths: pair (i,j) of batch item b is allowed only if j < len[b]
  *     (every query row is still produced); a row with no allowed pair gives zeros;
+ *     with `skip_padded_rows` the padded vectors are left out as queries as well:
+ *     a pair also needs i < len[b], so rows i >= len[b] are zeros (the paper has no
+ *     padding; this is Sec. 5.1's rule, "what is masked is not computed", applied to
+ *     both sides of a pair);
  *   - in the q = k = v scheme the shared vectors are z = x.Wq (or x itself when
  *     Wq is NULL and d_model = n_heads * d_k).
  *
@@ -46,6 +50,7 @@ enum { ORC_PLAIN = 0, ORC_NOSKIP = 1, ORC_SKIP = 2 };
 typedef struct {
     int32_t batch, n, d_model, n_heads, d_k, p;
     double scale;
+    int32_t skip_padded_rows;     /* with key lengths: rows i >= len take part in no pair */
 } orc_cfg;
 
 typedef struct {
@@ -57,9 +62,10 @@ typedef struct {
     uint64_t pairs_executed;      /* tiles_executed * (n/P)^2 */
 } orc_counts;
 
-static int allowed(int scheme, int i, int j, int len)
+static int allowed(int scheme, int i, int j, int len, int rows_too)
 {
     if (j >= len) return 0;                        /* key padding */
+    if (rows_too && i >= len) return 0;            /* query padding, when asked for */
     if (scheme == ORC_CAUSAL && j > i) return 0;   /* Sec. 5.1: main diagonal and below */
     return 1;
 }
@@ -203,7 +209,7 @@ int attn_oracle_forward(const orc_cfg *c, const double *X, const double *Wq, con
 #pragma omp for schedule(dynamic, 4)
                 for (int i = 0; i < n; ++i) {
                     for (int j = 0; j < n; ++j) {
-                        use[j] = (unsigned char)allowed(scheme, i, j, len);
+                        use[j] = (unsigned char)allowed(scheme, i, j, len, c->skip_padded_rows);
                         if (scheme == ORC_SYMMETRIC && variant == ORC_SKIP)
                             s[j] = S[(size_t)i * n + j];
                         else if (use[j] || variant == ORC_NOSKIP)
@@ -264,7 +270,7 @@ int attn_oracle_head_rows(const orc_cfg *c, const double *X, const double *Wq, c
         for (int r = 0; r < nrows; ++r) {
             const int i = rows[r];
             for (int j = 0; j < n; ++j) {
-                use[j] = (unsigned char)allowed(scheme, i, j, len);
+                use[j] = (unsigned char)allowed(scheme, i, j, len, c->skip_padded_rows);
                 s[j] = use[j] ? c->scale * dot(q + (size_t)i * d, k + (size_t)j * d, d) : 0.0;
             }
             row_softmax_pv(s, use, n, d, v, ORC_PLAIN, out + (size_t)r * d, NULL);
@@ -303,7 +309,7 @@ int attn_oracle_counts(const orc_cfg *c, int scheme, const int32_t *lens, orc_co
         memset(tile, 0, (size_t)P * P);
         for (int i = 0; i < n; ++i)
             for (int j = 0; j < n; ++j) {
-                if (!allowed(scheme, i, j, len)) continue;
+                if (!allowed(scheme, i, j, len, c->skip_padded_rows)) continue;
                 if (scheme == ORC_SYMMETRIC) {
                     if (i >= j) need[0]++;          /* one per unordered pair */
                     if (sym_computed(i, j, n)) sched[0]++;

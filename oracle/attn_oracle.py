@@ -24,7 +24,7 @@ PLAIN, NOSKIP, SKIP = 0, 1, 2
 class OrcCfg(C.Structure):
     _fields_ = [("batch", C.c_int32), ("n", C.c_int32), ("d_model", C.c_int32),
                 ("n_heads", C.c_int32), ("d_k", C.c_int32), ("p", C.c_int32),
-                ("scale", C.c_double)]
+                ("scale", C.c_double), ("skip_padded_rows", C.c_int32)]
 
 
 class OrcCounts(C.Structure):
@@ -78,8 +78,8 @@ def _iptr(a: Optional[np.ndarray]):
     return a.ctypes.data_as(C.POINTER(C.c_int32))
 
 
-def _cfg(batch, n, d_model, n_heads, d_k, p, scale) -> OrcCfg:
-    return OrcCfg(batch, n, d_model, n_heads, d_k, p, float(scale))
+def _cfg(batch, n, d_model, n_heads, d_k, p, scale, skip_padded_rows=False) -> OrcCfg:
+    return OrcCfg(batch, n, d_model, n_heads, d_k, p, float(scale), 1 if skip_padded_rows else 0)
 
 
 def _f64(a):
@@ -97,12 +97,12 @@ class OracleError(RuntimeError):
 
 
 def forward(X, Wq, Wk, Wv, *, n_heads: int, d_k: int, p: int, scheme: int, scale: float,
-            lens=None, variant: int = PLAIN, return_weights: bool = False):
+            lens=None, variant: int = PLAIN, return_weights: bool = False, skip_padded_rows: bool = False):
     """out [B,n,H*d_k] (and weights [B,H,n,n] if asked) in float64."""
     X = _f64(X)
     B, n, D = X.shape
     Wq, Wk, Wv, lens = _f64(Wq), _f64(Wk), _f64(Wv), _i32(lens)
-    cfg = _cfg(B, n, D, n_heads, d_k, p, scale)
+    cfg = _cfg(B, n, D, n_heads, d_k, p, scale, skip_padded_rows)
     out = np.zeros((B, n, n_heads * d_k), dtype=np.float64)
     w = np.zeros((B, n_heads, n, n), dtype=np.float64) if return_weights else None
     rc = lib().attn_oracle_forward(C.byref(cfg), _dptr(X), _dptr(Wq), _dptr(Wk), _dptr(Wv),
@@ -113,12 +113,12 @@ def forward(X, Wq, Wk, Wv, *, n_heads: int, d_k: int, p: int, scheme: int, scale
 
 
 def head_rows(X, Wq, Wk, Wv, *, n_heads: int, d_k: int, p: int, scheme: int, scale: float,
-              b: int, h: int, rows: Sequence[int], lens=None) -> np.ndarray:
+              b: int, h: int, rows: Sequence[int], lens=None, skip_padded_rows: bool = False) -> np.ndarray:
     """Rows `rows` of head h of batch item b: float64 [len(rows), d_k]."""
     X = _f64(X)
     B, n, D = X.shape
     Wq, Wk, Wv, lens = _f64(Wq), _f64(Wk), _f64(Wv), _i32(lens)
-    cfg = _cfg(B, n, D, n_heads, d_k, p, scale)
+    cfg = _cfg(B, n, D, n_heads, d_k, p, scale, skip_padded_rows)
     rows = np.ascontiguousarray(rows, dtype=np.int32)
     out = np.zeros((len(rows), d_k), dtype=np.float64)
     rc = lib().attn_oracle_head_rows(C.byref(cfg), _dptr(X), _dptr(Wq), _dptr(Wk), _dptr(Wv),
@@ -129,8 +129,8 @@ def head_rows(X, Wq, Wk, Wv, *, n_heads: int, d_k: int, p: int, scheme: int, sca
 
 
 def counts(*, batch: int, n: int, n_heads: int, p: int, scheme: int, lens=None,
-           d_model: int = 1, d_k: int = 1) -> dict:
-    cfg = _cfg(batch, n, d_model, n_heads, d_k, p, 1.0)
+           d_model: int = 1, d_k: int = 1, skip_padded_rows: bool = False) -> dict:
+    cfg = _cfg(batch, n, d_model, n_heads, d_k, p, 1.0, skip_padded_rows)
     st = OrcCounts()
     rc = lib().attn_oracle_counts(C.byref(cfg), scheme, _iptr(_i32(lens)), C.byref(st))
     if rc:

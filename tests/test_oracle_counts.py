@@ -96,6 +96,31 @@ def test_padded_workload_lengths():
     assert c["pairs_needed"][0] == closed
 
 
+@pytest.mark.parametrize("lens", [[0], [1], [5], [16], [40], [3, 16, 9, 0]])
+def test_counts_when_padded_rows_are_left_out(lens):
+    """Queries past the key length out as well: a len x len problem per batch item."""
+    n, p = 16, 4
+    lens = np.array(lens, dtype=np.int32)
+    Ls = [int(min(L, n)) for L in lens]
+    c = orc.counts(batch=len(lens), n=n, n_heads=2, p=p, scheme=orc.CAUSAL, lens=lens, skip_padded_rows=True)
+    assert c["pairs_needed"] == [2 * sum(L * (L + 1) // 2 for L in Ls)] * 3
+    T = [-(-L // (n // p)) for L in Ls]
+    assert c["tiles_executed"] == 2 * sum(t * (t + 1) // 2 for t in T)
+    f = orc.counts(batch=len(lens), n=n, n_heads=2, p=p, scheme=orc.FULL, lens=lens, skip_padded_rows=True)
+    assert f["pairs_needed"] == [2 * sum(L * L for L in Ls)] * 3
+    assert f["tiles_executed"] == 2 * sum(t * t for t in T)
+    # without key lengths the switch changes nothing
+    assert orc.counts(batch=2, n=n, n_heads=1, p=p, scheme=orc.CAUSAL, skip_padded_rows=True) == \
+        orc.counts(batch=2, n=n, n_heads=1, p=p, scheme=orc.CAUSAL)
+
+
+def test_padded_workload_strict_count():
+    w = inputs.WORKLOADS["padded"]
+    lens = inputs.draw_lengths(w)
+    c = orc.counts(batch=w.batch, n=w.n, n_heads=1, p=w.p, scheme=orc.CAUSAL, lens=lens, skip_padded_rows=True)
+    assert c["pairs_needed"][0] == sum(int(L) * (int(L) + 1) // 2 for L in lens) == 31887155
+
+
 def test_bad_partition_rejected():
     with pytest.raises(orc.OracleError) as e:
         orc.counts(batch=1, n=10, n_heads=1, p=4, scheme=orc.FULL)

@@ -224,6 +224,30 @@ def test_zero_length_gives_zero_rows_and_errors():
     assert e.value.code == 3
 
 
+@pytest.mark.parametrize("scheme", [orc.FULL, orc.CAUSAL])
+def test_padded_rows_left_out(scheme):
+    """With skip_padded_rows a batch item of key length L is the L-vector problem: its first L rows
+    equal the result for the first L vectors alone, its other rows are zero."""
+    rng = np.random.default_rng(11)
+    B, n, D, H, d = 3, 12, 10, 2, 4
+    X = rng.standard_normal((B, n, D))
+    Wq, Wk, Wv = (rng.standard_normal((D, H * d)) for _ in range(3))
+    lens = np.array([5, 12, 0], dtype=np.int32)
+    kw = dict(n_heads=H, d_k=d, scheme=scheme, scale=0.5)
+    got = orc.forward(X, Wq, Wk, Wv, p=4, lens=lens, skip_padded_rows=True, **kw)
+    for b, L in enumerate(lens):
+        assert np.all(got[b, L:] == 0.0)
+        if L:
+            alone = orc.forward(X[b:b + 1, :L], Wq, Wk, Wv, p=1, **kw)
+            assert np.array_equal(got[b, :L], alone[0])
+    # rows below the key length do not depend on the switch
+    keep = orc.forward(X, Wq, Wk, Wv, p=4, lens=lens, **kw)
+    for b, L in enumerate(lens):
+        assert np.array_equal(got[b, :L], keep[b, :L])
+    rows = orc.head_rows(X, Wq, Wk, Wv, p=4, lens=lens, b=0, h=1, rows=[0, 4, 5, 11], skip_padded_rows=True, **kw)
+    assert np.array_equal(rows, got[0, [0, 4, 5, 11], d:2 * d])
+
+
 def test_large_scores_do_not_overflow():
     """Eq. (2) is shift-invariant; scores far above exp's range must still give finite rows."""
     X = np.array([[[40.0], [30.0]]])
