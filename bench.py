@@ -49,18 +49,20 @@ def kernel_sources_sha256() -> str:
 METRIC = "useful attention TFLOP/s (post-skip) + % bf16 MFMA peak, 1 MI355X"
 
 
-def needed_pairs(w, lens):
-    """Pairs phase 1 must touch, all batch items and heads (closed forms)."""
+def needed_pairs(w, lens, rows_too=False):
+    """Pairs phase 1 must touch, all batch items and heads (closed forms).  rows_too: query rows
+    past the key length are left out as well."""
     n = w.n
     from paper_2012_01114_amd import inputs
+    Ls = [int(L) for L in (lens if lens is not None else [n] * w.batch)]
     if w.scheme == inputs.SCHEME_CAUSAL:
-        per = [int(L) * (int(L) + 1) // 2 + (n - int(L)) * int(L) for L in (lens if lens is not None else [n] * w.batch)]
+        per = [L * (L + 1) // 2 + (0 if rows_too else (n - L) * L) for L in Ls]
     else:
-        per = [n * int(L) for L in (lens if lens is not None else [n] * w.batch)]
+        per = [(L if rows_too else n) * L for L in Ls]
     return sum(per) * w.n_heads
 
 
-def cpu_baseline(w, f64, lens, budget_s=12.0, max_heads=256):
+def cpu_baseline(w, f64, lens, budget_s=12.0, max_heads=256, rows_too=False):
     """Time the CPU checker on (batch, head) pairs, 256 sampled rows each, until about
     `budget_s` seconds of CPU work have been spent."""
     from oracle import attn_oracle as orc
@@ -76,11 +78,13 @@ def cpu_baseline(w, f64, lens, budget_s=12.0, max_heads=256):
         rows = sorted(int(r) for r in rng.choice(w.n, size=min(256, w.n), replace=False))
         t0 = time.perf_counter()
         orc.head_rows(f64["X"], f64["Wq"], f64["Wk"], f64["Wv"], n_heads=w.n_heads, d_k=w.d_k, p=w.p,
-                      scheme=w.scheme, scale=w.d_k ** -0.5, b=b, h=h, rows=rows, lens=lens)
+                      scheme=w.scheme, scale=w.d_k ** -0.5, b=b, h=h, rows=rows, lens=lens,
+                      skip_padded_rows=rows_too)
         t_total += time.perf_counter() - t0
         L = w.n if lens is None else int(lens[b])
         from paper_2012_01114_amd import inputs
-        pairs = sum(min(r + 1, L) if w.scheme == inputs.SCHEME_CAUSAL else L for r in rows)
+        pairs = sum((min(r + 1, L) if w.scheme == inputs.SCHEME_CAUSAL else L) for r in rows
+                    if not (rows_too and r >= L))
         flop += 2.0 * w.d_model * w.d_k * (2 * w.n + len(rows)) + 4.0 * w.d_k * pairs
         picks.append((b, h))
     return {"value": flop / t_total / 1e12, "unit": "TFLOP/s", "cores": orc.num_threads(), "kind": "oracle",
@@ -96,6 +100,9 @@ def main():
     ap.add_argument("--warmup", type=int, default=10)
     ap.add_argument("--workload", default="long", help="tiny|encoder|causal|long|padded")
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--skip-padded-rows", action="store_true",
+                    help="padded workload: leave the padded vectors out as queries too (ATTN_FLAG_SKIP_PADDED_ROWS); "
+                         "the useful FLOPs shrink accordingly")
     ap.add_argument("--tiles", default="auto", choices=["auto", "wide", "narrow"],
                     help="attention kernel choice (default: the library's own)")
     ap.add_argument("--copy-probe", type=int, default=0, metavar="MIB",
@@ -133,6 +140,9 @@ def main():
     out = torch.empty(w.batch, w.n, w.hd, dtype=X.dtype, device=dev)
     dt = ar.ATTN_F32 if w.dtype == "f32" else ar.ATTN_BF16
     flags = {"auto": 0, "wide": ar.ATTN_FLAG_WIDE_TILES, "narrow": ar.ATTN_FLAG_NARROW_TILES}[args.tiles]
+    rows_too = args.skip_padded_rows and lens is not None
+    if rows_too:
+        flags |= ar.ATTN_FLAG_SKIP_PADDED_ROWS
     ctx = ar.attn_init(w.batch, w.n, w.d_model, w.n_heads, w.d_k, w.p, dt, 0.0, flags)
     ar.attn_set_key_lengths(ctx, lens_dev)
     stream = torch.cuda.current_stream(dev)
@@ -154,12 +164,13 @@ def main():
     stats = ar.attn_stats(ctx)
 
     ms_step = (t1 - t0) * 1e3 / args.steps
-    pairs = needed_pairs(w, lens)
+    pairs = needed_pairs(w, lens, rows_too)
     assert pairs == stats["pairs_needed"][0], (pairs, stats["pairs_needed"])
     attn_flop = 4.0 * w.d_k * pairs
     # projection: every q row, and the k and v rows that some allowed pair uses (those below the key length)
     kv_rows = w.batch * w.n if lens is None else int(np.minimum(np.maximum(lens, 0), w.n).sum())
-    proj_flop = 2.0 * (w.batch * w.n + 2 * kv_rows) * w.d_model * w.hd
+    q_rows = kv_rows if rows_too else w.batch * w.n
+    proj_flop = 2.0 * (q_rows + 2 * kv_rows) * w.d_model * w.hd
     value = (attn_flop + proj_flop) / (ms_step * 1e-3) / 1e12
 
     kern = {
@@ -169,7 +180,7 @@ def main():
     dom = max(kern, key=lambda k: kern[k]["ms"])
     achieved = kern[dom]["flop"] / (kern[dom]["ms"] * 1e-3) / 1e12
     traffic = None
-    if args.tiles == "auto" and kernel_sources_sha256() == TRAFFIC_SOURCES_SHA256:
+    if args.tiles == "auto" and not rows_too and kernel_sources_sha256() == TRAFFIC_SOURCES_SHA256:
         traffic = TRAFFIC_BYTES.get(w.name, {}).get(dom)
     roofline = {"kernel": dom, "bound": "mfma", "achieved": round(achieved, 2), "peak": MFMA_BF16_PEAK_TFLOPS,
                 "unit": "TFLOP/s", "frac": round(achieved / MFMA_BF16_PEAK_TFLOPS, 4), "traffic": traffic,
@@ -186,7 +197,8 @@ def main():
         "pct_bf16_mfma_peak": round(100.0 * value / MFMA_BF16_PEAK_TFLOPS, 2),
         "config": {"workload": f"{w.name}: batch {w.batch}, n {w.n}, d_model {w.d_model}, heads {w.n_heads}, "
                                f"d_k {w.d_k}, scheme {inputs.SCHEME_NAMES[w.scheme]}, P {w.p}"
-                               + (", key lengths from seed" if lens is not None else ""),
+                               + (", key lengths from seed" if lens is not None else "")
+                               + (", padded rows left out" if rows_too else ""),
                    "needed_pairs": pairs, "full_pairs": stats["pairs_full"],
                    "tiles_executed": stats["tiles_executed"], "tiles_full": stats["tiles_full"]},
         "roofline": roofline,
@@ -195,7 +207,7 @@ def main():
     torch.cuda.synchronize()
     ar.attn_destroy(ctx)
     if not args.no_cpu_baseline:
-        line["cpu_baseline"] = cpu_baseline(w, f64, lens)
+        line["cpu_baseline"] = cpu_baseline(w, f64, lens, rows_too=rows_too)
     print(json.dumps(line))
 
 

@@ -68,7 +68,13 @@ enum { ATTN_FLAG_NO_SKIP = 1u,
         * (4 wavefronts): WIDE asks for 256 rows (8 wavefronts), NARROW for 128.  d_k = 128
         * always takes 256 rows.  Results obey the same bars. */
        ATTN_FLAG_WIDE_TILES = 2u,
-       ATTN_FLAG_NARROW_TILES = 4u };
+       ATTN_FLAG_NARROW_TILES = 4u,
+       /* With key lengths: the padded vectors are left out as queries too.  A pair (i, j) of
+        * batch item b then also needs i < len[b]; rows i >= len[b] of `out` are written as zeros,
+        * their q rows are not projected, and the counts are those of the len x len problems.
+        * (Sec. 5.1's rule - what is masked is not computed - applied to both sides of a pair.)
+        * No effect without key lengths. */
+       ATTN_FLAG_SKIP_PADDED_ROWS = 8u };
 
 typedef struct {
     int32_t batch;     /* >= 1 */

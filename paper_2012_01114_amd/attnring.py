@@ -20,6 +20,7 @@ ATTN_F32, ATTN_BF16 = 0, 1
 ATTN_FLAG_NO_SKIP = 1
 ATTN_FLAG_WIDE_TILES = 2
 ATTN_FLAG_NARROW_TILES = 4
+ATTN_FLAG_SKIP_PADDED_ROWS = 8
 
 EXPORTS = ("attn_init", "attn_set_key_lengths", "attn_forward", "attn_stats", "attn_profile",
            "attn_profile_read", "attn_last_error", "attn_destroy")

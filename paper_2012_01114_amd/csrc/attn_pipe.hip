@@ -213,6 +213,7 @@ void attn_pipe_kernel(Problem pb, CountCfg cc, const bf16_t* __restrict__ q, con
     const int N = pb.N, Npad = pb.Npad;
     int len = N;
     if (pb.lens) { len = pb.lens[bb]; len = len < 0 ? 0 : (len > N ? N : len); }
+    const int rlen = pb.skip_rows ? len : N;  // query rows at or past it take part in no pair
     const int nkt_all = Npad / BC;
 
     const bf16_t* qh = q + (size_t)bh * Npad * DK;
@@ -234,19 +235,34 @@ void attn_pipe_kernel(Problem pb, CountCfg cc, const bf16_t* __restrict__ q, con
     unsigned long long cnt_logical = 0;  // per lane; summed over the wavefront at the end
     unsigned cnt_phys = 0;               // wave-uniform
 
-    const int n_pass = CAUSAL ? 2 : 1;
+    // Masked scheme: workgroup x takes row tiles T-1-x and x (Sec. 5.2).  With padded rows left
+    // out, T counts the row tiles that hold a row below the key length, so that the pairing
+    // balances the rows that are there; the row tiles past them only have zeros written, by two
+    // more passes with no walk.
+    const bool repair = CAUSAL && pb.skip_rows && !pb.noskip;
+    const int n_live = repair ? (rlen + BR - 1) / BR : n_qtiles;
+    const int n_pass = CAUSAL ? (repair ? 4 : 2) : 1;
 #pragma nounroll
     for (int pass = 0; pass < n_pass; ++pass) {
         int I;
+        bool zeros_only = false;
         if (CAUSAL) {
-            I = pass == 0 ? n_qtiles - 1 - x : x;
-            if (pass == 1 && x == n_qtiles - 1 - x) break;
+            if (pass < 2) {
+                I = pass == 0 ? n_live - 1 - x : x;
+                // no such pair; the lower tile of a pair is a pass of its own only below the upper one
+                if (n_live - 1 - x < x || (pass == 1 && x == n_live - 1 - x)) continue;
+            } else {
+                I = n_live + (pass - 2) * per_head + x;
+                if (I >= n_qtiles) continue;
+                zeros_only = true;
+            }
         } else {
             I = x;
         }
         const int i0w = I * BR + wave * 32;  // first row of this wavefront
         const int i = i0w + ln;              // this lane's query row
-        const bool wave_active = i0w < N;
+        const bool wave_active = i0w < (pb.noskip ? N : rlen);
+        const bool cut_rows = rlen < i0w + 32;  // some of this wavefront's rows are left out: test every pair
 
         // The walk over 64-key tiles.  Needed tiles are J = 0 .. nJ-1.
         //   masked scheme: J = Js, Js-1, .., 0 (own diagonal tile first);
@@ -256,6 +272,7 @@ void attn_pipe_kernel(Problem pb, CountCfg cc, const bf16_t* __restrict__ q, con
         // Inside a tile the upper 32 keys come first, so key offsets fall along the masked walk.
         int nJ = (len + BC - 1) / BC;
         if (CAUSAL) nJ = nJ < (I + 1) * (BR / BC) ? nJ : (I + 1) * (BR / BC);
+        if (zeros_only) nJ = 0;
         const int n_dead = pb.noskip ? nkt_all - nJ : 0;
         const int nT = nJ + n_dead;
         const int has_cut = (!CAUSAL && (len % BC) != 0) ? 1 : 0;
@@ -274,7 +291,7 @@ void attn_pipe_kernel(Problem pb, CountCfg cc, const bf16_t* __restrict__ q, con
         auto key_of_block = [&](int n) -> int { return tile_of_step(n >> 1) * BC + 32 * (1 - (n & 1)); };
         auto block_needed = [&](int kb) -> bool { return pb.noskip || (kb < len && (!CAUSAL || kb <= i0w)); };
         auto block_is_edge = [&](int kb) -> bool {
-            return pb.noskip || kb + 32 > len || (CAUSAL && kb + 31 > i0w);
+            return pb.noskip || cut_rows || kb + 32 > len || (CAUSAL && kb + 31 > i0w);
         };
         // The blocks a wavefront leaves out lie at the head of the walk, its edge blocks follow,
         // the rest are blocks in which every pair is allowed.
@@ -287,7 +304,8 @@ void attn_pipe_kernel(Problem pb, CountCfg cc, const bf16_t* __restrict__ q, con
         // ---- counts: logical tiles whose first pair is allowed ----
         if (n_first < NB) {
             cnt_phys += (unsigned)(NB - n_first);
-            const unsigned nr_anchor = cdiv_b(min(i0w + 32, N), cc) - cdiv_b(min(i0w, N), cc);
+            const int rcnt = pb.noskip ? N : rlen;  // rows that anchor counted tiles
+            const unsigned nr_anchor = cdiv_b(min(i0w + 32, rcnt), cc) - cdiv_b(min(i0w, rcnt), cc);
             if (pb.noskip) {
                 if (lane == 0) cnt_logical += (unsigned long long)nr_anchor * cdiv_b(N, cc);
             } else {
@@ -298,7 +316,7 @@ void attn_pipe_kernel(Problem pb, CountCfg cc, const bf16_t* __restrict__ q, con
                 if (lane == 0) cnt_logical += (unsigned long long)nr_anchor * cdiv_b(k_int, cc);
                 // the rest (diagonal block, block cut by the key length): pair by pair
                 const int k_end = CAUSAL ? (len < i0w + 32 ? len : i0w + 32) : len;
-                if (g == 0 && i < N && is_multiple(i, cc)) {
+                if (g == 0 && i < rlen && is_multiple(i, cc)) {
 #pragma nounroll
                     for (int j = (int)cdiv_b(k_int, cc) * cc.b; j < k_end; j += cc.b)
                         cnt_logical += (!CAUSAL || j <= i) ? 1u : 0u;
@@ -368,6 +386,7 @@ void attn_pipe_kernel(Problem pb, CountCfg cc, const bf16_t* __restrict__ q, con
                 }
                 int lim_base = len - 1;  // the lane's last allowed key
                 if (CAUSAL) lim_base = lim_base < i ? lim_base : i;
+                if (i >= rlen) lim_base = -1;  // a row that is left out has no allowed key
                 lim_base -= 4 * g;
 
                 // E(n) for the upper (UPPER = 1: first block of a tile) or lower 32 keys of tile t

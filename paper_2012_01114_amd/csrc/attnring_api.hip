@@ -73,6 +73,7 @@ Problem make_problem(const attn_ctx* c, int scheme)
     pb.B = c->cfg.batch; pb.N = c->cfg.n; pb.D = c->cfg.d_model; pb.H = c->cfg.n_heads; pb.d = c->cfg.d_k;
     pb.P = c->cfg.p; pb.b = c->b; pb.Npad = c->Npad; pb.scale = c->scale; pb.scheme = scheme;
     pb.noskip = (c->cfg.flags & ATTN_FLAG_NO_SKIP) != 0;
+    pb.skip_rows = (c->cfg.flags & ATTN_FLAG_SKIP_PADDED_ROWS) != 0 && c->lens != nullptr;
     pb.is_bf16 = c->cfg.dtype == ATTN_BF16;
     pb.lens = c->lens;
     pb.counters = c->counters;
@@ -149,7 +150,8 @@ attn_status attn_init(const attn_config* cfg, attn_ctx** out_ctx)
         return fail(nullptr, ATTN_ERR_INVALID, "attn_init: every size must be >= 1%s");
     if (cfg->dtype != ATTN_F32 && cfg->dtype != ATTN_BF16)
         return fail(nullptr, ATTN_ERR_INVALID, "attn_init: unknown dtype%s");
-    if (cfg->flags & ~(uint32_t)(ATTN_FLAG_NO_SKIP | ATTN_FLAG_WIDE_TILES | ATTN_FLAG_NARROW_TILES))
+    if (cfg->flags & ~(uint32_t)(ATTN_FLAG_NO_SKIP | ATTN_FLAG_WIDE_TILES | ATTN_FLAG_NARROW_TILES |
+                                 ATTN_FLAG_SKIP_PADDED_ROWS))
         return fail(nullptr, ATTN_ERR_INVALID, "attn_init: unknown flag%s");
     if ((cfg->flags & ATTN_FLAG_WIDE_TILES) && (cfg->flags & ATTN_FLAG_NARROW_TILES))
         return fail(nullptr, ATTN_ERR_INVALID, "attn_init: WIDE_TILES and NARROW_TILES exclude each other%s");
@@ -343,9 +345,11 @@ attn_status attn_stats(attn_ctx* ctx, attn_stats_t* out)
     out->tiles_full = B * H * P * P;
     attn_status st = ATTN_OK;
     unsigned long long per_head_sum = 0;
+    const bool rows_too = (cf.flags & ATTN_FLAG_SKIP_PADDED_ROWS) != 0 && ctx->lens != nullptr;
     switch (ctx->last_scheme) {
     case ATTN_SCHEME_FULL:  // Sec. 3.2: n^2 per phase; with key padding n*len
-        st = sum_over_lengths(ctx, [n](unsigned long long L) { return n * L; }, &per_head_sum);
+        st = sum_over_lengths(ctx, [n, rows_too](unsigned long long L) { return (rows_too ? L : n) * L; },
+                              &per_head_sum);
         for (int ph = 0; ph < 3; ++ph) out->pairs_needed[ph] = out->pairs_scheduled[ph] = H * per_head_sum;
         break;
     case ATTN_SCHEME_SYMMETRIC:  // Sec. 4.1 / 4.2: phase 1 n(n+1)/2 needed, n(n+2)/2 scheduled for even n
@@ -355,7 +359,8 @@ attn_status attn_stats(attn_ctx* ctx, attn_stats_t* out)
         break;
     default:  // Sec. 5.1: n(n+1)/2 in all phases; with key padding sum_i min(i+1, len)
         st = sum_over_lengths(
-            ctx, [n](unsigned long long L) { return L * (L + 1) / 2 + (n - L) * L; }, &per_head_sum);
+            ctx, [n, rows_too](unsigned long long L) { return L * (L + 1) / 2 + (rows_too ? 0ull : (n - L) * L); },
+            &per_head_sum);
         for (int ph = 0; ph < 3; ++ph) out->pairs_needed[ph] = out->pairs_scheduled[ph] = H * per_head_sum;
         break;
     }

@@ -19,6 +19,7 @@ struct Problem {
     float scale;         // multiplies the raw scores
     int scheme;
     bool noskip;         // debug: visit every tile, mask with -inf
+    bool skip_rows;      // with key lengths: rows i >= len take part in no pair and give zeros
     bool is_bf16;        // storage type of X, W, out
     const int* lens;     // device, [B] or nullptr
     unsigned long long* counters;  // device: CNT_SLOTS slots of (logical tiles, physical score blocks), then totals

@@ -151,14 +151,16 @@ __device__ __forceinline__ void store_row(const RowState& st, T* out, size_t bas
     }
 }
 
-__device__ __forceinline__ bool pair_allowed(int scheme, int i, int j, int len)
+// len: key length of the batch item; rlen: the same limit for query rows when padded rows are left
+// out, else n.
+__device__ __forceinline__ bool pair_allowed(int scheme, int i, int j, int len, int rlen)
 {
-    return j < len && (scheme != SCHEME_CAUSAL || j <= i);
+    return j < len && i < rlen && (scheme != SCHEME_CAUSAL || j <= i);
 }
-// A b x b tile holds a needed pair iff its lowest-left pair is allowed.
-__device__ __forceinline__ bool tile_needed(int scheme, int I, int J, int b, int len)
+// A b x b tile holds a needed pair iff its first row's pair with its first key is allowed.
+__device__ __forceinline__ bool tile_needed(int scheme, int I, int J, int b, int len, int rlen)
 {
-    return J * b < len && (scheme != SCHEME_CAUSAL || J <= I);
+    return J * b < len && I * b < rlen && (scheme != SCHEME_CAUSAL || J <= I);
 }
 
 // ---------------------------------------------------------------------------
@@ -176,6 +178,7 @@ __global__ __launch_bounds__(256) void attn_generic_kernel(Problem pb, const flo
     const int N = pb.N, d = pb.d, b = pb.b, P = pb.P;
     int len = N;
     if (pb.lens) { len = pb.lens[bb]; len = len < 0 ? 0 : (len > N ? N : len); }
+    const int rlen = pb.skip_rows ? len : N;
     const size_t head = ((size_t)bb * pb.H + h) * (size_t)N * d;
     const float* qh = q + head;
     const float* kh = k + head;
@@ -185,7 +188,7 @@ __global__ __launch_bounds__(256) void attn_generic_kernel(Problem pb, const flo
         unsigned long long tiles = 0;
         for (int t = 0; t < P; ++t) {
             int J = I - t; if (J < 0) J += P;
-            if (pb.noskip || tile_needed(pb.scheme, I, J, b, len)) ++tiles;
+            if (pb.noskip || tile_needed(pb.scheme, I, J, b, len, rlen)) ++tiles;
         }
         count_add(pb.counters, (blockIdx.z * gridDim.y + blockIdx.y) * gridDim.x + blockIdx.x, tiles, tiles);
     }
@@ -199,7 +202,7 @@ __global__ __launch_bounds__(256) void attn_generic_kernel(Problem pb, const flo
         for (int a = 0; a < MAX_ACC; ++a) st.o[a] = 0.f;
         for (int t = 0; t < P; ++t) {  // ring order, own block first
             int J = I - t; if (J < 0) J += P;
-            if (!pb.noskip && !tile_needed(pb.scheme, I, J, b, len)) continue;  // redundant tile: skipped
+            if (!pb.noskip && !tile_needed(pb.scheme, I, J, b, len, rlen)) continue;  // redundant tile: skipped
             for (int c0 = 0; c0 < b; c0 += 64) {
                 const int cnt = (b - c0) < 64 ? (b - c0) : 64;
                 const int j = J * b + c0 + lane;
@@ -210,7 +213,7 @@ __global__ __launch_bounds__(256) void attn_generic_kernel(Problem pb, const flo
                     for (int l = 0; l < d; ++l) s = fmaf(qr[l], kr[l], s);  // Eq. (1)
                     s *= pb.scale;
                 }
-                fold_chunk(st, s, valid && pair_allowed(pb.scheme, i, j, len), J * b + c0, cnt, vh, d, lane);
+                fold_chunk(st, s, valid && pair_allowed(pb.scheme, i, j, len, rlen), J * b + c0, cnt, vh, d, lane);
             }
         }
         store_row(st, out, ((size_t)bb * N + i) * ((size_t)pb.H * d) + (size_t)h * d, d, lane);

@@ -149,7 +149,7 @@ __global__ __launch_bounds__(256) void proj_mfma_kernel(int Bsz, int N, int Npad
                                                         const bf16_t* __restrict__ X,
                                                         const bf16_t* __restrict__ Wt, bf16_t* __restrict__ qo,
                                                         bf16_t* __restrict__ ko, bf16_t* __restrict__ vto,
-                                                        int tiles_x, int tiles_w, float qscale, const int* __restrict__ lens)
+                                                        int tiles_x, int tiles_w, float qscale, const int* __restrict__ lens, bool skip_q_rows)
 {
     constexpr int WT = BT / 2;          // wavefront tile edge
     constexpr int NB = WT / 32;         // MFMA blocks per edge
@@ -174,7 +174,8 @@ __global__ __launch_bounds__(256) void proj_mfma_kernel(int Bsz, int N, int Npad
     const bool is_v = w0 >= 2 * HD;
     // Keys past the key length of their batch item are in no allowed pair (Sec. 5.1 applied to
     // padding): their k and v rows are not computed.  (q rows are: every query row has an output.)
-    if (lens != nullptr && w0 >= HD && past_key_length(lens, x0, Npad, N)) return;
+    // With padded rows left out as queries too, the same holds for their q rows.
+    if (lens != nullptr && (w0 >= HD || skip_q_rows) && past_key_length(lens, x0, Npad, N)) return;
 
     // per-thread source rows: chunk ch = tid + 256*u -> row ch/8, k-chunk ch%8
     const int kc = tid & 7;
@@ -315,7 +316,7 @@ template <int BT, int WR, int WC>
 __global__ __launch_bounds__(64 * WR * WC, (WR * WC) / 4 * (BT == 256 ? 1 : 2))
 void proj_dma_kernel(int Bsz, int N, int Npad, int D, int H, int d, const bf16_t* __restrict__ X,
                      const bf16_t* __restrict__ Wt, bf16_t* __restrict__ qo, bf16_t* __restrict__ ko,
-                     bf16_t* __restrict__ vto, int tiles_x, int tiles_w, float qscale, const int* __restrict__ lens)
+                     bf16_t* __restrict__ vto, int tiles_x, int tiles_w, float qscale, const int* __restrict__ lens, bool skip_q_rows)
 {
     constexpr int NW = WR * WC;
     constexpr int TA = BT / WR, TB = BT / WC;    // wavefront tile: TA rows of the A side, TB of the B side
@@ -345,7 +346,8 @@ void proj_dma_kernel(int Bsz, int N, int Npad, int D, int H, int d, const bf16_t
     const bool is_v = w0 >= 2 * HD;
     // Keys past the key length of their batch item are in no allowed pair (Sec. 5.1 applied to
     // padding): their k and v rows are not computed.  (q rows are: every query row has an output.)
-    if (lens != nullptr && w0 >= HD && past_key_length(lens, x0, Npad, N)) return;
+    // With padded rows left out as queries too, the same holds for their q rows.
+    if (lens != nullptr && (w0 >= HD || skip_q_rows) && past_key_length(lens, x0, Npad, N)) return;
 
     // Source byte offsets of this lane for its pieces (piece m = wave + NW*u holds rows
     // 16m..16m+15; the lane lands at row 16m + lane/4, chunk position lane%4, and fetches the chunk
@@ -577,7 +579,7 @@ hipError_t launch_dma(const Problem& pb, const bf16_t* X, const bf16_t* Wt, bf16
     const int tiles_w = 3 * pb.H * pb.d / BT;
     const int grid = ((tiles_x * tiles_w + 7) / 8) * 8;
     hipLaunchKernelGGL((proj_dma_kernel<BT, WR, WC>), dim3(grid), dim3(64 * WR * WC), 0, s, pb.B, pb.N, pb.Npad, pb.D,
-                       pb.H, pb.d, X, Wt, q, k, vt, tiles_x, tiles_w, qscale, pb.noskip ? nullptr : pb.lens);
+                       pb.H, pb.d, X, Wt, q, k, vt, tiles_x, tiles_w, qscale, pb.noskip ? nullptr : pb.lens, pb.skip_rows);
     return hipGetLastError();
 }
 
@@ -590,7 +592,7 @@ hipError_t launch_bt(const Problem& pb, const bf16_t* X, const bf16_t* Wt, bf16_
     const int tiles_w = 3 * pb.H * pb.d / BT;
     const int grid = ((tiles_x * tiles_w + 7) / 8) * 8;
     hipLaunchKernelGGL(proj_mfma_kernel<BT>, dim3(grid), dim3(256), 0, s, pb.B, pb.N, pb.Npad, pb.D, pb.H, pb.d, X, Wt,
-                       q, k, vt, tiles_x, tiles_w, qscale, pb.noskip ? nullptr : pb.lens);
+                       q, k, vt, tiles_x, tiles_w, qscale, pb.noskip ? nullptr : pb.lens, pb.skip_rows);
     return hipGetLastError();
 }
 

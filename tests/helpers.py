@@ -65,8 +65,8 @@ def oracle_forward(w, f64, scheme, scale, lens=None, **kw):
                        scheme=scheme, scale=default_scale(w, scale), lens=lens, **kw)
 
 
-def oracle_counts(w, scheme, lens=None):
-    return orc.counts(batch=w.batch, n=w.n, n_heads=w.n_heads, p=w.p, scheme=scheme, lens=lens)
+def oracle_counts(w, scheme, lens=None, **kw):
+    return orc.counts(batch=w.batch, n=w.n, n_heads=w.n_heads, p=w.p, scheme=scheme, lens=lens, **kw)
 
 
 def check_counts(stats, ref, noskip=False):

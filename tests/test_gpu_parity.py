@@ -170,6 +170,61 @@ def test_key_lengths_change_between_calls(scheme):
         run.close()
 
 
+# ---- padded vectors left out as queries too (ATTN_FLAG_SKIP_PADDED_ROWS) -------------------------
+@pytest.mark.parametrize("case", [
+    ("f32", 3, 48, 32, 2, 16, 6, 0),                                   # float path
+    ("bf16", 3, 320, 64, 2, 64, 40, ar.ATTN_FLAG_NARROW_TILES),        # 128-row workgroups
+    ("bf16", 3, 704, 128, 2, 64, 88, ar.ATTN_FLAG_WIDE_TILES),         # 256-row workgroups, d_k = 64
+    ("bf16", 3, 600, 192, 1, 128, 75, 0),                              # d_k = 128
+])
+@pytest.mark.parametrize("scheme", [FULL, CAUSAL])
+def test_padded_rows_left_out(case, scheme):
+    dtype, B, n, D, H, d, p, tiles = case
+    w = hp.custom_workload("skip_rows", B, n, D, H, d, p, dtype, scheme, 500 + n)
+    stored, f64 = inputs.make_inputs(w)
+    for lens in (np.array([n // 3 + 1, n, 0], dtype=np.int32), np.array([33, 1, n - 1], dtype=np.int32)):
+        print(f"[lens] {lens.tolist()}", flush=True)
+        stored["lens"] = lens
+        outs = []
+        for noskip in (0, ar.ATTN_FLAG_NO_SKIP):
+            run = hp.GpuRun(w, stored, flags=tiles | ar.ATTN_FLAG_SKIP_PADDED_ROWS | noskip)
+            try:
+                got, stats = run.forward(scheme)
+            finally:
+                run.close()
+            hp.tol_check(got, hp.oracle_forward(w, f64, scheme, 0.0, lens=lens, skip_padded_rows=True), w.dtype)
+            hp.check_counts(stats, hp.oracle_counts(w, scheme, lens, skip_padded_rows=True), noskip=bool(noskip))
+            for b, L in enumerate(lens):
+                assert np.all(got[b, L:] == 0.0)
+            outs.append(got)
+        assert np.array_equal(outs[0], outs[1])
+
+
+def test_padded_workload_with_padded_rows_left_out():
+    w = inputs.WORKLOADS["padded"]
+    lens = inputs.draw_lengths(w)
+    stored, f64 = inputs.make_inputs(w)
+    stored["lens"] = lens
+    run = hp.GpuRun(w, stored, flags=ar.ATTN_FLAG_SKIP_PADDED_ROWS)
+    try:
+        got, stats = run.forward(w.scheme)
+    finally:
+        run.close()
+    assert np.all(np.isfinite(got))
+    for b, L in enumerate(lens):
+        assert np.all(got[b, L:] == 0.0)
+    for (b, h) in [(0, 0), (13, 7), (31, 15)]:
+        L = int(lens[b])
+        rows = sorted({0, L // 2, L - 1, min(L, w.n - 1), w.n - 1})
+        print(f"[rows] b={b} h={h} len={L} rows={rows}", flush=True)
+        ref = orc.head_rows(f64["X"], f64["Wq"], f64["Wk"], f64["Wv"], n_heads=w.n_heads, d_k=w.d_k, p=w.p,
+                            scheme=w.scheme, scale=hp.default_scale(w, 0.0), b=b, h=h, rows=rows, lens=lens,
+                            skip_padded_rows=True)
+        hp.tol_check(got[b, rows, h * w.d_k:(h + 1) * w.d_k], ref, w.dtype)
+    hp.check_counts(stats, hp.oracle_counts(w, w.scheme, lens, skip_padded_rows=True))
+    assert stats["pairs_needed"][0] == 16 * 31887155
+
+
 # ---- workloads 4 and 5: sampled rows + counts + a property that holds at any size --------------
 def _sampled_rows(w, lens, picks):
     stored, f64 = inputs.make_inputs(w)
