@@ -1,4 +1,4 @@
-"""The paper's ring schedules as index streams (Yu & Fujita, Algorithms 1 and 3).
+"""The paper's ring schedules as index streams (Yu & Fujita, Algorithms 1, 2 and 3).
 
 TEST INFRASTRUCTURE ONLY, like the rest of oracle/: nothing in the product imports it.
 
@@ -61,6 +61,26 @@ def baseline_phase2(n: int, m: int) -> Iterator[Tuple[int, int, int, int]]:
         if (i, j) != last:
             cycle, last = cycle + 1, (i, j)
         yield cycle, l, _rotating(l, j, i, m), _component(l, j, i, m, n)
+
+
+def symmetric_phase1(n: int, m: int) -> Iterator[Tuple[int, int, int, int, int]]:
+    """Algorithm 2, phase 1 (Sec. 4.2), the computing slots only: stage h computes the circulant
+    diagonal at distance h from the main one, one element of every symmetric pair; on which side of
+    the main diagonal depends on h % m, which decides the direction the result is later passed in.
+    For even n a last stage computes the diagonal n/2 in full (the balance trade-off).  The extra
+    transfer cycles that copy w'_AB to w'_BA are not enumerated."""
+    half = (n - 1) // 2 if n % 2 else n // 2 - 1
+    stages = [(h, h if (h % m) <= m / 2 else -h) for h in range(0, half + 1)]
+    if n % 2 == 0:
+        stages.append((n // 2, n // 2))
+    cycle = 0
+    for _, shift in stages:
+        last = None
+        for i, j, l in _sweeps(n, m):
+            if (i, j) != last:
+                cycle, last = cycle + 1, (i, j)
+            b = (_rotating(l, j, i, m) - 2) % n + 1
+            yield cycle, l, (b + shift - 1) % n + 1, b, _component(l, j, i, m, n)
 
 
 def masked_phase1(n: int, m: int) -> Iterator[Tuple[int, int, int, int, int]]:

@@ -20,6 +20,29 @@ def test_baseline_covers_every_product_once(n, m):
     assert len(pairs) == n * n and set(pairs.values()) == {1}
 
 
+@pytest.mark.parametrize("n,m", SHAPES + [(15, 5), (15, 15)])
+def test_symmetric_computes_one_of_every_pair(n, m):
+    """Sec. 4.1 / 4.2: n(n+1)/2 scores computed for odd n; for even n the diagonal n/2 is computed
+    from both sides, n(n+2)/2 in all."""
+    seen = Counter((min(a, b), max(a, b), c) for _, _, a, b, c in rs.symmetric_phase1(n, m))
+    assert set(seen) == {(a, b, c) for a in range(1, n + 1) for b in range(a, n + 1) for c in range(1, n + 1)}
+    twice = {(a, b) for (a, b, _), k in seen.items() if k == 2}
+    assert set(seen.values()) <= {1, 2}
+    assert twice == ({(a, a + n // 2) for a in range(1, n // 2 + 1)} if n % 2 == 0 else set())
+    computed = sum(seen.values()) // n
+    ref = orc.counts(batch=1, n=n, n_heads=1, p=m, scheme=orc.SYMMETRIC)
+    assert computed == ref["pairs_scheduled"][0] == (n * (n + 1) // 2 if n % 2 else n * (n + 2) // 2)
+    assert len(seen) // n == ref["pairs_needed"][0]
+
+
+@pytest.mark.parametrize("n,m,printed", [(3, 3, 21), (4, 4, 36)])
+def test_symmetric_cycles_where_no_reuse_transfer_is_needed(n, m, printed):
+    """Table 1, Algo.2: the two rows whose stages all have h % m <= 1 need no extra transfer cycle,
+    and the computing cycles alone give the printed numbers."""
+    total = rs.cycles(rs.symmetric_phase1(n, m)) + 2 * (n // m) * n + rs.cycles(rs.baseline_phase1(n, m))
+    assert total == printed
+
+
 @pytest.mark.parametrize("n,m", SHAPES)
 def test_masked_covers_the_lower_triangle_once(n, m):
     seen = Counter((a, b, c) for _, _, a, b, c in rs.masked_phase1(n, m) if a)
@@ -58,7 +81,7 @@ def test_partial_sums_move_to_the_next_pe(n, m):
 
 @pytest.mark.parametrize("n,m", SHAPES)
 def test_no_operand_pair_twice_in_a_cycle(n, m):
-    for stream in (rs.baseline_phase1(n, m), rs.masked_phase1(n, m)):
+    for stream in (rs.baseline_phase1(n, m), rs.masked_phase1(n, m), rs.symmetric_phase1(n, m)):
         per_cycle = Counter((cyc, a, b, c) for cyc, _, a, b, c in stream if a)
         assert set(per_cycle.values()) == {1}
 
