@@ -34,6 +34,7 @@ struct attn_ctx {
     // timing
     bool prof_on;
     int prof_calls;
+    std::vector<unsigned char> prof_prepared;  // per recorded call: a kernel ran before the projection
     std::vector<hipEvent_t> events;  // 4 per timed call
     char err[512];
 };
@@ -259,6 +260,7 @@ attn_status attn_forward(attn_ctx* ctx, const void* X, const void* Wq, const voi
     if (e != hipSuccess) return hip_fail(ctx, what_, e);
 
     MARK(0);
+    bool prepared = false;  // whether event 1 of this call gets recorded
 
     const bool use_mfma = ctx->mfma_shape && scheme != ATTN_SCHEME_SYMMETRIC && aligned_to(X, 16) &&
                           aligned_to(out, 8) && aligned_to(Wq, 2) && aligned_to(Wk, 2) && aligned_to(Wv, 2);
@@ -268,10 +270,16 @@ attn_status attn_forward(attn_ctx* ctx, const void* X, const void* Wq, const voi
         CHECK("launch zero_counters");
     }
     if (use_mfma) {
-        e = launch_transpose_w(pb, (const bf16_t*)Wq, (const bf16_t*)Wk, (const bf16_t*)Wv, ctx->wt, s);
-        CHECK("launch transpose_w");
-        MARK(1);
-        e = launch_proj_mfma(pb, (const bf16_t*)X, ctx->wt, ctx->qb, ctx->kb, ctx->vtb, s);
+        // the first kernel of the call clears the counter slots: the projection itself when it reads
+        // the weights in place, else the weight re-layout
+        if (!proj_reads_weights_in_place(pb, (const bf16_t*)Wq, (const bf16_t*)Wk, (const bf16_t*)Wv)) {
+            e = launch_transpose_w(pb, (const bf16_t*)Wq, (const bf16_t*)Wk, (const bf16_t*)Wv, ctx->wt, s);
+            CHECK("launch transpose_w");
+            MARK(1);
+            prepared = true;
+        }
+        e = launch_proj_mfma(pb, (const bf16_t*)X, (const bf16_t*)Wq, (const bf16_t*)Wk, (const bf16_t*)Wv, ctx->wt,
+                             ctx->qb, ctx->kb, ctx->vtb, s);
         CHECK("launch proj_mfma");
         MARK(2);
         // d_k = 64: 128-row workgroups of 4 wavefronts, three of them per CU; d_k = 128: 256 rows, 8 wavefronts
@@ -286,6 +294,7 @@ attn_status attn_forward(attn_ctx* ctx, const void* X, const void* Wq, const voi
         attn_status st = ensure_generic_workspace(ctx);
         if (st != ATTN_OK) return st;
         MARK(1);
+        prepared = true;
         if (scheme == ATTN_SCHEME_SYMMETRIC) {
             const size_t bytes = (size_t)cf.batch * cf.n_heads * cf.n * cf.n * sizeof(float);
             if (bytes > MAX_SCORE_BYTES)
@@ -316,7 +325,11 @@ attn_status attn_forward(attn_ctx* ctx, const void* X, const void* Wq, const voi
     }
 #undef MARK
 #undef CHECK
-    if (ev) ctx->prof_calls += 1;
+    if (ev) {
+        if (ctx->prof_prepared.size() <= (size_t)ctx->prof_calls) ctx->prof_prepared.resize((size_t)ctx->prof_calls + 1);
+        ctx->prof_prepared[(size_t)ctx->prof_calls] = prepared ? 1 : 0;
+        ctx->prof_calls += 1;
+    }
     ctx->last_stream = s;
     ctx->last_scheme = scheme;
     ctx->have_forward = true;
@@ -394,13 +407,16 @@ attn_status attn_profile_read(attn_ctx* ctx, attn_profile_t* out)
     hipError_t e = hipStreamSynchronize(ctx->last_stream);
     if (e != hipSuccess) return hip_fail(ctx, "hipStreamSynchronize", e);
     double sum[3] = {0, 0, 0};
-    for (int c = 0; c < ctx->prof_calls; ++c)
-        for (int k = 0; k < 3; ++k) {
+    for (int c = 0; c < ctx->prof_calls; ++c) {
+        const bool prepared = ctx->prof_prepared[(size_t)c] != 0;
+        for (int k = prepared ? 0 : 1; k < 3; ++k) {
             float ms = 0.f;
-            e = hipEventElapsedTime(&ms, ctx->events[(size_t)c * 4 + k], ctx->events[(size_t)c * 4 + k + 1]);
+            const int from = (k == 1 && !prepared) ? 0 : k;  // no kernel before the projection: it starts at event 0
+            e = hipEventElapsedTime(&ms, ctx->events[(size_t)c * 4 + from], ctx->events[(size_t)c * 4 + k + 1]);
             if (e != hipSuccess) return hip_fail(ctx, "hipEventElapsedTime", e);
             sum[k] += ms;
         }
+    }
     out->calls = ctx->prof_calls;
     out->ms_prepare = (float)(sum[0] / ctx->prof_calls);
     out->ms_projection = (float)(sum[1] / ctx->prof_calls);

@@ -53,8 +53,9 @@ hipError_t launch_sym_generic(const Problem& pb, const float* z, float* scores, 
 // with the keys of every 16-block stored in MFMA operand order.
 hipError_t launch_transpose_w(const Problem& pb, const bf16_t* Wq, const bf16_t* Wk, const bf16_t* Wv,
                               bf16_t* Wt, hipStream_t s);
-hipError_t launch_proj_mfma(const Problem& pb, const bf16_t* X, const bf16_t* Wt, bf16_t* q, bf16_t* k,
-                            bf16_t* vt, hipStream_t s);
+bool proj_reads_weights_in_place(const Problem& pb, const bf16_t* Wq, const bf16_t* Wk, const bf16_t* Wv);
+hipError_t launch_proj_mfma(const Problem& pb, const bf16_t* X, const bf16_t* Wq, const bf16_t* Wk,
+                            const bf16_t* Wv, const bf16_t* Wt, bf16_t* q, bf16_t* k, bf16_t* vt, hipStream_t s);
 // Fused phases 1-3 with redundant blocks left out; `waves` wavefronts of 32 rows per workgroup:
 // 4 or 8 for d_k = 64, 8 for d_k = 128.
 hipError_t launch_attn_pipe(const Problem& pb, const bf16_t* q, const bf16_t* k, const bf16_t* vt,

@@ -5,9 +5,12 @@
 //   q, k : [B][H][Npad][d]            (row = vector, d contiguous)
 //   v^T  : [B][H][Npad/64][d][64]     (per 64-key block, key contiguous, and the
 //                                      keys of each 16-group in MFMA operand order)
-// The weights arrive as [D][H*d] (q = x.W); a small kernel first lays them out
-// as W^T [3*H*d][D] so that both GEMM operands are contiguous along the
-// contraction index, which is what the MFMA operand registers want.
+// The weights arrive as [D][H*d] (q = x.W), i.e. contiguous along the output
+// columns, while an MFMA operand register wants 8 consecutive values of the
+// contraction index.  The main kernel leaves them where they are and turns them
+// while reading LDS (ds_read_b64_tr_b16); the fallback kernel for shapes and
+// alignments that kernel does not take has a small kernel lay them out as
+// W^T [3*H*d][D] first.
 #include "mfma_common.h"
 
 namespace attnring {
@@ -315,8 +318,10 @@ __global__ __launch_bounds__(256) void proj_mfma_kernel(int Bsz, int N, int Npad
 template <int BT, int WR, int WC>
 __global__ __launch_bounds__(64 * WR * WC, (WR * WC) / 4 * (BT == 256 ? 1 : 2))
 void proj_dma_kernel(int Bsz, int N, int Npad, int D, int H, int d, const bf16_t* __restrict__ X,
-                     const bf16_t* __restrict__ Wt, bf16_t* __restrict__ qo, bf16_t* __restrict__ ko,
-                     bf16_t* __restrict__ vto, int tiles_x, int tiles_w, float qscale, const int* __restrict__ lens, bool skip_q_rows)
+                     const bf16_t* __restrict__ Wq, const bf16_t* __restrict__ Wk, const bf16_t* __restrict__ Wv,
+                     bf16_t* __restrict__ qo, bf16_t* __restrict__ ko, bf16_t* __restrict__ vto, int tiles_x,
+                     int tiles_w, float qscale, const int* __restrict__ lens, bool skip_q_rows,
+                     unsigned long long* __restrict__ counters)
 {
     constexpr int NW = WR * WC;
     constexpr int TA = BT / WR, TB = BT / WC;    // wavefront tile: TA rows of the A side, TB of the B side
@@ -327,7 +332,11 @@ void proj_dma_kernel(int Bsz, int N, int Npad, int D, int H, int d, const bf16_t
     constexpr int PPW = (BT / 16) / NW;          // 1 KiB pieces (16 rows) per wavefront, side and slot
     constexpr int PER_SLICE = 4 * PPW;           // requests of one wavefront per 64-deep slice
     static_assert(PPW >= 1 && PER_SLICE <= 15, "piece count fits the wavefront count and the vmcnt field");
+    constexpr int WROWB = BT * 2;                // bytes of one k-row of the weight side in a slot
+    constexpr int WCPR = WROWB / 16;             // its 16-byte chunks
+    constexpr int WRPP = 64 / WCPR;              // k-rows per 1 KiB piece
     __shared__ __attribute__((aligned(1024))) unsigned char lds[NSLOT * SLOT];
+    clear_counters(counters);  // this is the first kernel of a forward pass on this path
 
     const int tid = threadIdx.x;
     const int lane = tid & 63, ln = lane & 31, g = lane >> 5;
@@ -349,10 +358,18 @@ void proj_dma_kernel(int Bsz, int N, int Npad, int D, int H, int d, const bf16_t
     // With padded rows left out as queries too, the same holds for their q rows.
     if (lens != nullptr && (w0 >= HD || skip_q_rows) && past_key_length(lens, x0, Npad, N)) return;
 
-    // Source byte offsets of this lane for its pieces (piece m = wave + NW*u holds rows
-    // 16m..16m+15; the lane lands at row 16m + lane/4, chunk position lane%4, and fetches the chunk
-    // that the swizzle puts there).  32 bits hold them (attn_init bounds the element counts), which
-    // lets a request take a uniform 64-bit base and this offset with no address arithmetic per lane.
+    // The weights stay in the caller's layout, W[k][column]: this tile's columns of the one matrix
+    // it lies in.
+    const int which = w0 / HD;
+    const bf16_t* Wm = (which == 0 ? Wq : (which == 1 ? Wk : Wv)) + (w0 - which * HD);
+
+    // Source byte offsets of this lane for its pieces.  32 bits hold them (attn_init bounds the
+    // element counts), which lets a request take a uniform 64-bit base and this offset.
+    //   x side: rows are vectors, 64 bytes (32 k) each; piece m = wave + NW*u holds rows
+    //           16m..16m+15; the lane lands at row 16m + lane/4, chunk position lane%4;
+    //   w side: rows are k, BT columns each; piece m holds k-rows m*WRPP..; the lane lands at
+    //           k-row m*WRPP + lane/WCPR, chunk position lane%WCPR.
+    // Either way it fetches the chunk that the swizzle of its row puts at that position.
     unsigned xoff[PPW], woff[PPW];
 #pragma unroll
     for (int u = 0; u < PPW; ++u) {
@@ -363,17 +380,20 @@ void proj_dma_kernel(int Bsz, int N, int Npad, int D, int H, int d, const bf16_t
         int i = xr - bb * Npad;
         i = i < N ? i : N - 1;
         xoff[u] = 2u * ((unsigned)(bb * N + i) * (unsigned)D + c * 8);
-        woff[u] = 2u * ((unsigned)(w0 + row) * (unsigned)D + c * 8);
+        const int kr = (wave + NW * u) * WRPP + lane / WCPR;
+        const int wc16 = (lane % WCPR) ^ (4 * (kr & 3));
+        woff[u] = 2u * ((unsigned)kr * (unsigned)HD + wc16 * 8);
     }
     const int x_side = is_v ? 0 : SIDE, w_side = is_v ? SIDE : 0;
     // Request number q (0 .. PER_SLICE-1) of the slice that starts at k0: piece u = q/4, operand
-    // q/2%2, half q%2 (the two halves of a row share a cache line and are requested back to back).
-    // The first half of the slice goes into slot s0, the second into slot s1.
+    // q/2%2, half q%2 (the two halves of an x row share a cache line and are requested back to
+    // back).  The first half of the slice goes into slot s0, the second into slot s1.
     auto request = [&](int q, int k0, int s0, int s1) {
         const int u = q >> 2, w_op = (q >> 1) & 1, h = q & 1;
         const int m = wave + NW * u;
         unsigned char* dst = lds + (h ? s1 : s0) * SLOT + m * 1024 + (w_op ? w_side : x_side);
-        const char* src = (const char*)((w_op ? Wt : X) + k0 + 32 * h) + (w_op ? woff[u] : xoff[u]);
+        const char* src = w_op ? (const char*)(Wm + (size_t)(k0 + 32 * h) * HD) + woff[u]
+                               : (const char*)(X + k0 + 32 * h) + xoff[u];
         __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void*)src,
                                          (__attribute__((address_space(3))) void*)dst, 16, 0, 0);
     };
@@ -382,13 +402,34 @@ void proj_dma_kernel(int Bsz, int N, int Npad, int D, int H, int d, const bf16_t
         for (int q = 0; q < PER_SLICE; ++q) request(q, k0, s0, s1);
     };
 
-    // LDS byte offsets of this lane's operand reads for the two k-steps of a slot, from the slot base.
-    int aoff[2], boff[2];
+    // LDS byte offsets of this lane's operand reads for the two k-steps of a slot, from the slot
+    // base, for the first 32-row block of the wavefront's share of each side.
+    //   x side: 128 bits = 8 k of row ln, chunk 2*ks + g.
+    //   w side: stored k-major, read with the transposing 64-bit LDS read: 16 lanes hand in the
+    //           addresses of a 4 (k) x 16 (columns) patch, four columns each, and lane i gets
+    //           column i of the patch, its four k values.  Lanes 16..31 take the next 16 columns,
+    //           the upper half of the wavefront the upper 8 k of the k-step; two reads (4 k each)
+    //           make one operand.  k-rows are BT*2 bytes apart, a multiple of the 256 bytes the
+    //           banks span, and LDS serves 32 lanes (two patches, 4 k x 32 columns) at a time, so
+    //           the chunks of k-row k are XOR-ed with 4*(k%4): the four 64-byte runs then fall on
+    //           different banks.  That XOR reaches bits 2 and 3 of the chunk index, which is also
+    //           where the 32-column block number sits: one table per block.
+    const int x_row0 = is_v ? wr * TA : wc * TB;  // first x row / first w column of this wavefront
+    const int w_col0 = is_v ? wc * TB : wr * TA;
+    constexpr int NWB = NA > NBK ? NA : NBK;  // 32-column blocks of the weight side of a wavefront
+    int xfo[2], wfo[NWB][2][2];
 #pragma unroll
     for (int ks = 0; ks < 2; ++ks) {
-        const int sw = ((2 * ks + g) ^ ((ln >> 2) & 3)) * 16;
-        aoff[ks] = (wr * TA + ln) * 64 + sw;
-        boff[ks] = SIDE + (wc * TB + ln) * 64 + sw;
+        xfo[ks] = x_side + (x_row0 + ln) * 64 + (((2 * ks + g) ^ ((ln >> 2) & 3)) << 4);
+#pragma unroll
+        for (int blk = 0; blk < NWB; ++blk)
+#pragma unroll
+            for (int r = 0; r < 2; ++r) {
+                const int i16 = lane & 15;
+                const int k = 16 * ks + 8 * g + 4 * r + (i16 >> 2);
+                const int col = w_col0 + 32 * blk + 16 * ((lane >> 4) & 1) + 4 * (i16 & 3);
+                wfo[blk][ks][r] = w_side + k * WROWB + (((col >> 3) ^ (4 * (k & 3))) << 4) + ((col & 7) << 1);
+            }
     }
 
     f32x16 acc[NA][NBK];
@@ -407,24 +448,46 @@ void proj_dma_kernel(int Bsz, int N, int Npad, int D, int H, int d, const bf16_t
     // would drain.  The order is pinned with scheduling fences; the group-barrier solver drops its
     // pattern as soon as memory requests are part of it.
     u32x4 af[2][NA], bf[2][NBK];
-    auto read_frag = [&](u32x4 (&fa)[NA], u32x4 (&fb)[NBK], int r, const unsigned char* pa, const unsigned char* pb) {
-        if (r == 0) fa[0] = *(const u32x4*)pa;
-        else if (r <= NBK) fb[r - 1] = *(const u32x4*)(pb + (r - 1) * 2048);
-        else fa[r - NBK] = *(const u32x4*)(pa + (r - NBK) * 2048);
+    auto x_frag = [&](const unsigned char* slot_base, int ks, int blk) -> u32x4 {
+        return *(const u32x4*)(slot_base + xfo[ks] + blk * 2048);
     };
-    auto load_frags = [&](u32x4 (&fa)[NA], u32x4 (&fb)[NBK], int slot, int ks) {
+    // The transposing reads are written out by hand: as a builtin, the compiler takes them to
+    // alias the copies into LDS that are still in flight and makes each of them wait for all of
+    // those (vmcnt(0)), which is the prefetch gone.  It does not count hand-written requests, so
+    // every k-step starts with its own wait for the LDS reads of the one before.
+    const unsigned lds_addr = (unsigned)(size_t)(__attribute__((address_space(3))) unsigned char*)lds;
+    auto w_frag = [&](const unsigned char* slot_base, int ks, int blk) -> u32x4 {
+        const unsigned base = lds_addr + (unsigned)(slot_base - lds);
+        u32x2 lo, hi;
+        asm volatile("ds_read_b64_tr_b16 %0, %1" : "=v"(lo) : "v"(base + (unsigned)wfo[blk][ks][0]));
+        asm volatile("ds_read_b64_tr_b16 %0, %1" : "=v"(hi) : "v"(base + (unsigned)wfo[blk][ks][1]));
+        return u32x4{lo[0], lo[1], hi[0], hi[1]};
+    };
+    // fragment number r of a k-step, in the order a0, b0.., a1..; the weights are the A side of q and
+    // k tiles and the B side of v tiles
+    auto read_frag = [&](auto is_v_, u32x4 (&fa)[NA], u32x4 (&fb)[NBK], int r, const unsigned char* slot_base,
+                         int ks) {
+        constexpr bool IS_V = decltype(is_v_)::value;
+        if (r == 0 || r > NBK) {
+            const int a = r == 0 ? 0 : r - NBK;
+            fa[a] = IS_V ? x_frag(slot_base, ks, a) : w_frag(slot_base, ks, a);
+        } else {
+            fb[r - 1] = IS_V ? w_frag(slot_base, ks, r - 1) : x_frag(slot_base, ks, r - 1);
+        }
+    };
+    auto load_frags = [&](auto is_v_, u32x4 (&fa)[NA], u32x4 (&fb)[NBK], int slot, int ks) {
 #pragma unroll
-        for (int r = 0; r < NA + NBK; ++r)
-            read_frag(fa, fb, r, lds + slot * SLOT + aoff[ks], lds + slot * SLOT + boff[ks]);
+        for (int r = 0; r < NA + NBK; ++r) read_frag(is_v_, fa, fb, r, lds + slot * SLOT, ks);
     };
-    auto kstep = [&](const u32x4 (&fa)[NA], const u32x4 (&fb)[NBK], u32x4 (&na)[NA], u32x4 (&nb)[NBK], int slot,
-                     int ks, auto nd_, int q0, int k0, int s0, int s1) {
+    auto kstep = [&](auto is_v_, const u32x4 (&fa)[NA], const u32x4 (&fb)[NBK], u32x4 (&na)[NA], u32x4 (&nb)[NBK],
+                     int slot, int ks, auto nd_, int q0, int k0, int s0, int s1) {
         constexpr int ND = decltype(nd_)::value;
         constexpr int NRD = NA + NBK, NMF = NA * NBK;
         static_assert(NRD % 2 == 0 && NRD / 2 <= NMF, "read pairs fit behind the MFMAs of a k-step");
         static_assert(ND <= NMF, "at most one request per MFMA");
-        const unsigned char* pa = lds + slot * SLOT + aoff[ks];
-        const unsigned char* pb = lds + slot * SLOT + boff[ks];
+        const unsigned char* slot_base = lds + slot * SLOT;
+        __builtin_amdgcn_sched_barrier(0);
+        __builtin_amdgcn_s_waitcnt(0xC07F);  // lgkmcnt(0): the fragments of this k-step are in
         __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
         for (int a = 0; a < NA; ++a)
@@ -433,8 +496,8 @@ void proj_dma_kernel(int Bsz, int N, int Npad, int D, int H, int d, const bf16_t
                 acc[a][b] = mfma32(fa[a], fb[b], acc[a][b]);
                 const int m = a * NBK + b + 1;  // MFMAs issued so far
                 if (m <= NRD / 2) {
-                    read_frag(na, nb, 2 * m - 2, pa, pb);
-                    read_frag(na, nb, 2 * m - 1, pa, pb);
+                    read_frag(is_v_, na, nb, 2 * m - 2, slot_base, ks);
+                    read_frag(is_v_, na, nb, 2 * m - 1, slot_base, ks);
                 }
                 if (ND > 0 && (m * ND) % NMF == 0) request(q0 + m * ND / NMF - 1, k0, s0, s1);
                 __builtin_amdgcn_sched_barrier(0);
@@ -448,20 +511,20 @@ void proj_dma_kernel(int Bsz, int N, int Npad, int D, int H, int d, const bf16_t
     // the first fragments of the next half slice are read while the second k-step's MFMAs run, so
     // the matrix pipe has work on both sides of the barrier.  With `more`, slice j+2 is requested
     // behind the first barrier, into the slot that the half slice before this one left and into sa.
-    auto slice = [&](auto more_, int j, int sa) {
+    auto slice = [&](auto is_v_, auto more_, int j, int sa) {
         constexpr bool MORE = decltype(more_)::value;
         constexpr std::integral_constant<int, MORE ? PER_SLICE / 2 : 0> nreq{};
         const int sb = next_slot(sa), sc = next_slot(sb), se = next_slot(next_slot(sc));
         const int k2 = (j + 2) * 64;
-        kstep(af[0], bf[0], af[1], bf[1], sa, 1, no_req, 0, 0, 0, 0);
+        kstep(is_v_, af[0], bf[0], af[1], bf[1], sa, 1, no_req, 0, 0, 0, 0);
         __builtin_amdgcn_s_waitcnt(0xC07F);  // lgkmcnt(0)
         __builtin_amdgcn_s_barrier();
-        kstep(af[1], bf[1], af[0], bf[0], sb, 0, nreq, 0, k2, se, sa);
-        kstep(af[0], bf[0], af[1], bf[1], sb, 1, nreq, PER_SLICE / 2, k2, se, sa);
+        kstep(is_v_, af[1], bf[1], af[0], bf[0], sb, 0, nreq, 0, k2, se, sa);
+        kstep(is_v_, af[0], bf[0], af[1], bf[1], sb, 1, nreq, PER_SLICE / 2, k2, se, sa);
         // lgkmcnt(0); slice j+1 has landed (loads return in order; slice j+2 may be in flight)
         __builtin_amdgcn_s_waitcnt(0x0070 | (MORE ? PER_SLICE : 0));
         __builtin_amdgcn_s_barrier();
-        kstep(af[1], bf[1], af[0], bf[0], sc, 0, no_req, 0, 0, 0, 0);  // reads ahead into slice j+1
+        kstep(is_v_, af[1], bf[1], af[0], bf[0], sc, 0, no_req, 0, 0, 0, 0);  // reads ahead into slice j+1
         return sc;
     };
 
@@ -474,13 +537,17 @@ void proj_dma_kernel(int Bsz, int N, int Npad, int D, int H, int d, const bf16_t
         __builtin_amdgcn_s_waitcnt(0x0F70);
     }
     __builtin_amdgcn_s_barrier();
-    load_frags(af[0], bf[0], 0, 0);
-    int sa = 0;  // slot of the first half of slice j
-    int j = 0;
+    auto all_slices = [&](auto is_v_) {
+        load_frags(is_v_, af[0], bf[0], 0, 0);
+        int sa = 0;  // slot of the first half of slice j
+        int j = 0;
 #pragma nounroll
-    for (; j + 2 < ns; ++j) sa = slice(std::true_type{}, j, sa);
+        for (; j + 2 < ns; ++j) sa = slice(is_v_, std::true_type{}, j, sa);
 #pragma nounroll
-    for (; j < ns; ++j) sa = slice(std::false_type{}, j, sa);
+        for (; j < ns; ++j) sa = slice(is_v_, std::false_type{}, j, sa);
+    };
+    if (is_v) all_slices(std::true_type{});
+    else all_slices(std::false_type{});
     __builtin_amdgcn_s_waitcnt(0x0070);  // the fragments read ahead for a slice that does not exist are dropped
     __builtin_amdgcn_s_barrier();
 
@@ -571,15 +638,16 @@ void proj_dma_kernel(int Bsz, int N, int Npad, int D, int H, int d, const bf16_t
 inline float q_prescale(const Problem& pb) { return pb.scale * 1.4426950408889634f; }
 
 template <int BT, int WR, int WC>
-hipError_t launch_dma(const Problem& pb, const bf16_t* X, const bf16_t* Wt, bf16_t* q, bf16_t* k, bf16_t* vt,
-                      hipStream_t s)
+hipError_t launch_dma(const Problem& pb, const bf16_t* X, const bf16_t* Wq, const bf16_t* Wk, const bf16_t* Wv,
+                      bf16_t* q, bf16_t* k, bf16_t* vt, hipStream_t s)
 {
     const float qscale = q_prescale(pb);
     const int tiles_x = pb.B * pb.Npad / BT;
     const int tiles_w = 3 * pb.H * pb.d / BT;
     const int grid = ((tiles_x * tiles_w + 7) / 8) * 8;
     hipLaunchKernelGGL((proj_dma_kernel<BT, WR, WC>), dim3(grid), dim3(64 * WR * WC), 0, s, pb.B, pb.N, pb.Npad, pb.D,
-                       pb.H, pb.d, X, Wt, q, k, vt, tiles_x, tiles_w, qscale, pb.noskip ? nullptr : pb.lens, pb.skip_rows);
+                       pb.H, pb.d, X, Wq, Wk, Wv, q, k, vt, tiles_x, tiles_w, qscale, pb.noskip ? nullptr : pb.lens,
+                       pb.skip_rows, pb.counters);
     return hipGetLastError();
 }
 
@@ -613,19 +681,27 @@ hipError_t launch_transpose_w(const Problem& pb, const bf16_t* Wq, const bf16_t*
     return hipGetLastError();
 }
 
-hipError_t launch_proj_mfma(const Problem& pb, const bf16_t* X, const bf16_t* Wt, bf16_t* q, bf16_t* k, bf16_t* vt,
-                            hipStream_t s)
+// Whether the projection reads the weights where the caller has them (no W^T, no re-layout
+// kernel): d_model in whole 64-deep slices, and 16-byte aligned weights for the 16-byte copies.
+bool proj_reads_weights_in_place(const Problem& pb, const bf16_t* Wq, const bf16_t* Wk, const bf16_t* Wv)
+{
+    const int HD = pb.H * pb.d;
+    const bool aligned16 = ((reinterpret_cast<uintptr_t>(Wq) | reinterpret_cast<uintptr_t>(Wk) |
+                             reinterpret_cast<uintptr_t>(Wv)) & 15) == 0;
+    return pb.D % 64 == 0 && HD % 128 == 0 && aligned16;
+}
+
+hipError_t launch_proj_mfma(const Problem& pb, const bf16_t* X, const bf16_t* Wq, const bf16_t* Wk,
+                            const bf16_t* Wv, const bf16_t* Wt, bf16_t* q, bf16_t* k, bf16_t* vt, hipStream_t s)
 {
     // Largest square tile that divides the per-matrix column count (so a tile never
-    // mixes q, k and v columns) and still gives every CU a few tiles.  (A ring of four 32-deep
-    // LDS stages with requests three slices ahead was measured slower than two 64-deep stages:
-    // twice the barriers, and request latency is not what holds this kernel back.)
+    // mixes q, k and v columns) and still gives every CU a few tiles.
     const int HD = pb.H * pb.d;
     const long rows = (long)pb.B * pb.Npad;
     const bool big = HD % 256 == 0 && rows % 256 == 0 && (rows / 256) * (3L * HD / 256) >= 512;
-    if (pb.D % 64 == 0) {  // k slices go straight to LDS
-        if (big) return launch_dma<256, 2, 4>(pb, X, Wt, q, k, vt, s);
-        if (HD % 128 == 0) return launch_dma<128, 2, 2>(pb, X, Wt, q, k, vt, s);
+    if (proj_reads_weights_in_place(pb, Wq, Wk, Wv)) {  // operands go straight to LDS
+        if (big) return launch_dma<256, 2, 4>(pb, X, Wq, Wk, Wv, q, k, vt, s);
+        return launch_dma<128, 2, 2>(pb, X, Wq, Wk, Wv, q, k, vt, s);
     }
     if (HD % 128 == 0) return launch_bt<128>(pb, X, Wt, q, k, vt, s);
     return launch_bt<64>(pb, X, Wt, q, k, vt, s);
