@@ -1,7 +1,7 @@
 """Benchmark of the whole self-attention call on one MI355X.
 
-One step = one attn_forward: weight re-layout, q/k/v projection GEMM and the
-fused score/softmax/weighted-sum kernel with redundancy skipping, on synthetic
+One step = one attn_forward: q/k/v projection GEMM and the fused
+score/softmax/weighted-sum kernel with redundancy skipping, on synthetic
 inputs already resident in HBM.  Prints ONE JSON line.
 
   value     useful TFLOP/s of the whole call: (projection FLOPs of the rows some

@@ -103,7 +103,8 @@ typedef struct {
 
 typedef struct {
     int32_t calls;            /* attn_forward calls timed since profiling was switched on */
-    float ms_prepare;         /* average per call: weight re-layout kernels */
+    float ms_prepare;         /* average per call: kernels ahead of the projection (weight re-layout on the
+                                 fallback path), 0 when there is none */
     float ms_projection;      /* average per call: q/k/v projection kernel(s) */
     float ms_attention;       /* average per call: score/softmax/weighted-sum kernel(s) */
 } attn_profile_t;

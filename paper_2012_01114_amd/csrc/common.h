@@ -49,8 +49,9 @@ hipError_t launch_attn_generic(const Problem& pb, const float* q, const float* k
 hipError_t launch_sym_generic(const Problem& pb, const float* z, float* scores, void* out, hipStream_t s);
 
 // ---- bf16 MFMA path (d_k 64 or 128, FULL and CAUSAL) -----------------------
-// Wt: [3][H*d][D] (transposed weights); q, k: [B][H][Npad][d]; vt: [B][H][d][Npad]
-// with the keys of every 16-block stored in MFMA operand order.
+// q, k: [B][H][Npad][d]; vt: [B][H][Npad/64][d][64] with the keys of every 16-group stored in MFMA
+// operand order.  Wt: [3][H*d][D], transposed weights, needed only when the projection cannot read
+// the weights in place (launch_transpose_w fills it, and is then the first kernel of the call).
 hipError_t launch_transpose_w(const Problem& pb, const bf16_t* Wq, const bf16_t* Wk, const bf16_t* Wv,
                               bf16_t* Wt, hipStream_t s);
 bool proj_reads_weights_in_place(const Problem& pb, const bf16_t* Wq, const bf16_t* Wk, const bf16_t* Wv);
