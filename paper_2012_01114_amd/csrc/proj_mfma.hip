@@ -89,6 +89,7 @@ __global__ __launch_bounds__(256) void transpose_w16_kernel(int D, int HD, const
 }
 
 // ---------------------------------------------------------------------------
+// Fallback GEMM (any d_model, any alignment), on transposed weights:
 // C = A . B^T with both operands k-contiguous.  Square BT x BT tile per
 // workgroup, 2 x 2 wavefronts, 32x32x16 MFMA blocks, 64-deep k slices double
 // buffered in LDS.  The "x side" rows are vectors (with the per-batch row pitch
@@ -302,18 +303,21 @@ __global__ __launch_bounds__(256) void proj_mfma_kernel(int Bsz, int N, int Npad
 }
 
 // ---------------------------------------------------------------------------
-// The same GEMM for d_model a multiple of 64, with the operands copied from
-// global memory straight into LDS (global_load_lds, 16 bytes per lane).
+// The GEMM for d_model a multiple of 64 and 16-byte aligned weights, with the operands
+// copied from global memory straight into LDS (global_load_lds, 16 bytes per lane) and
+// the weights taken in the caller's layout.
 //
 // A request for 64 KiB of operands takes longer to come back than the MFMAs of one
 // 64-deep slice take to run, so two slices have to be in flight.  LDS cannot hold
 // three 64-deep stages of a 256 x 256 tile; it holds five 32-deep ones.  They form a
 // ring of slots; a slice is requested as two half slices into the two slots that the
 // half slices four and five behind it have left, which gives a request one and a half
-// slice periods to land.  A slot row is 64 bytes (32 bf16); its four 16-byte chunks
-// are XOR-swizzled with bits 2..3 of the row index, which keeps the 128-bit operand
-// reads of 16 consecutive rows on distinct banks.  WR x WC wavefronts share a BT x BT
-// tile.
+// slice periods to land.  A slot holds the x side as BT rows of 64 bytes (32 k of a
+// vector), its four 16-byte chunks XOR-swizzled with bits 2..3 of the row index,
+// which keeps the 128-bit operand reads of 16 consecutive rows on distinct banks, and
+// the weight side as it lies in memory, 32 k-rows of BT columns, read with the
+// transposing LDS read (see the offset tables in the kernel).  WR x WC wavefronts
+// share a BT x BT tile.
 // ---------------------------------------------------------------------------
 template <int BT, int WR, int WC>
 __global__ __launch_bounds__(64 * WR * WC, (WR * WC) / 4 * (BT == 256 ? 1 : 2))
