@@ -392,14 +392,21 @@ void proj_dma_kernel(int Bsz, int N, int Npad, int D, int H, int d, const bf16_t
     // Request number q (0 .. PER_SLICE-1) of the slice that starts at k0: piece u = q/4, operand
     // q/2%2, half q%2 (the two halves of an x row share a cache line and are requested back to
     // back).  The first half of the slice goes into slot s0, the second into slot s1.
+    // Buffer addressing: descriptor base + the lane's 32-bit offset + a scalar offset for the
+    // slice, so that a request costs no vector instruction for its address.
+    const __amdgpu_buffer_rsrc_t x_rsrc = __builtin_amdgcn_make_buffer_rsrc((void*)X, 0, -1, 0x00020000);
+    const __amdgpu_buffer_rsrc_t w_rsrc = __builtin_amdgcn_make_buffer_rsrc((void*)Wm, 0, -1, 0x00020000);
     auto request = [&](int q, int k0, int s0, int s1) {
         const int u = q >> 2, w_op = (q >> 1) & 1, h = q & 1;
         const int m = wave + NW * u;
         unsigned char* dst = lds + (h ? s1 : s0) * SLOT + m * 1024 + (w_op ? w_side : x_side);
-        const char* src = w_op ? (const char*)(Wm + (size_t)(k0 + 32 * h) * HD) + woff[u]
-                               : (const char*)(X + k0 + 32 * h) + xoff[u];
-        __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void*)src,
-                                         (__attribute__((address_space(3))) void*)dst, 16, 0, 0);
+        const unsigned kk = (unsigned)(k0 + 32 * h);
+        if (w_op)
+            __builtin_amdgcn_raw_ptr_buffer_load_lds(w_rsrc, (__attribute__((address_space(3))) void*)dst, 16,
+                                                     (int)woff[u], (int)(2u * kk * (unsigned)HD), 0, 0);
+        else
+            __builtin_amdgcn_raw_ptr_buffer_load_lds(x_rsrc, (__attribute__((address_space(3))) void*)dst, 16,
+                                                     (int)xoff[u], (int)(2u * kk), 0, 0);
     };
     auto issue = [&](int k0, int s0, int s1) {
 #pragma unroll
