@@ -428,19 +428,17 @@ void proj_dma_kernel(int Bsz, int N, int Npad, int D, int H, int d, const bf16_t
     const int x_row0 = is_v ? wr * TA : wc * TB;  // first x row / first w column of this wavefront
     const int w_col0 = is_v ? wc * TB : wr * TA;
     constexpr int NWB = NA > NBK ? NA : NBK;  // 32-column blocks of the weight side of a wavefront
-    int xfo[2], wfo[NWB][2][2];
+    int xfo[2], wfo[NWB];  // w side: k-step 0, first read; the others lie whole k-rows further (same k % 4)
 #pragma unroll
     for (int ks = 0; ks < 2; ++ks) {
         xfo[ks] = x_side + (x_row0 + ln) * 64 + (((2 * ks + g) ^ ((ln >> 2) & 3)) << 4);
+    }
 #pragma unroll
-        for (int blk = 0; blk < NWB; ++blk)
-#pragma unroll
-            for (int r = 0; r < 2; ++r) {
-                const int i16 = lane & 15;
-                const int k = 16 * ks + 8 * g + 4 * r + (i16 >> 2);
-                const int col = w_col0 + 32 * blk + 16 * ((lane >> 4) & 1) + 4 * (i16 & 3);
-                wfo[blk][ks][r] = w_side + k * WROWB + (((col >> 3) ^ (4 * (k & 3))) << 4) + ((col & 7) << 1);
-            }
+    for (int blk = 0; blk < NWB; ++blk) {
+        const int i16 = lane & 15;
+        const int k = 8 * g + (i16 >> 2);
+        const int col = w_col0 + 32 * blk + 16 * ((lane >> 4) & 1) + 4 * (i16 & 3);
+        wfo[blk] = w_side + k * WROWB + (((col >> 3) ^ (4 * (k & 3))) << 4) + ((col & 7) << 1);
     }
 
     f32x16 acc[NA][NBK];
@@ -468,10 +466,10 @@ void proj_dma_kernel(int Bsz, int N, int Npad, int D, int H, int d, const bf16_t
     // every k-step starts with its own wait for the LDS reads of the one before.
     const unsigned lds_addr = (unsigned)(size_t)(__attribute__((address_space(3))) unsigned char*)lds;
     auto w_frag = [&](const unsigned char* slot_base, int ks, int blk) -> u32x4 {
-        const unsigned base = lds_addr + (unsigned)(slot_base - lds);
+        const unsigned addr = lds_addr + (unsigned)(slot_base - lds) + (unsigned)wfo[blk];
         u32x2 lo, hi;
-        asm volatile("ds_read_b64_tr_b16 %0, %1" : "=v"(lo) : "v"(base + (unsigned)wfo[blk][ks][0]));
-        asm volatile("ds_read_b64_tr_b16 %0, %1" : "=v"(hi) : "v"(base + (unsigned)wfo[blk][ks][1]));
+        asm volatile("ds_read_b64_tr_b16 %0, %1 offset:%2" : "=v"(lo) : "v"(addr), "n"(16 * ks * WROWB));
+        asm volatile("ds_read_b64_tr_b16 %0, %1 offset:%2" : "=v"(hi) : "v"(addr), "n"((16 * ks + 4) * WROWB));
         return u32x4{lo[0], lo[1], hi[0], hi[1]};
     };
     // fragment number r of a k-step, in the order a0, b0.., a1..; the weights are the A side of q and
