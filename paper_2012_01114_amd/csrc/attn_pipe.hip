@@ -30,8 +30,8 @@
 // Online softmax with a lazily raised reference.  q arrives pre-multiplied by
 // scale*log2(e) and the score MFMAs start from minus the row's reference, so the
 // MFMA yields the base-2 exponent itself and an exponential costs one v_exp_f32;
-// row sums take two bf16 weights per v_dot2c.  The reference is raised only when a score
-// exceeds it by more than 2^RAISE (rare after the first blocks); until then
+// row sums are plain fp32 additions (dot instructions stall on the matrix pipe).
+// The reference is raised only when a score exceeds it by more than 2^RAISE (rare after the first blocks); until then
 // exponentials may reach 2^RAISE, which fp32 sums and bf16 operands hold without
 // loss.  Raising rescales the row at the head of E(n), when everything computed
 // with the old reference has been added to O.
@@ -62,9 +62,13 @@ struct Pipe {
     static constexpr int VPIECES = V_BYTES / 1024 / WAVES;
     static constexpr int PPW = KPIECES + VPIECES;
     // LDS ring, in 64-key tiles.  Three stages let three 4-wavefront workgroups of d_k = 64 share a
-    // CU (three wavefronts per SIMD); otherwise four stages and two wavefronts per SIMD.
-    static constexpr int STAGES = (DK == 64 && WAVES == 4) ? 3 : 4;
+    // CU (three wavefronts per SIMD); otherwise five stages (all 160 KiB at d_k = 128) and two
+    // wavefronts per SIMD.
+    static constexpr int STAGES = (DK == 64 && WAVES == 4) ? 3 : 5;
     static constexpr int OCC = (DK == 64 && WAVES == 4) ? 3 : 2;
+    // With five stages a wavefront in the walk does not request a tile right behind the barrier
+    // that frees its stage but spreads its pieces over the matrix phases up to the next barrier.
+    static constexpr bool SPREAD = STAGES >= 5;
     // Fold the reference into the score accumulator (saves a subtraction per pair, costs 16 registers):
     // pays where the vector ALUs are the busier unit per MFMA, d_k = 128.
     static constexpr bool USE_CNEG = DK == 128;
@@ -120,20 +124,30 @@ struct Pipe {
     }
     // Phase 1 (Eq. (1)) of one block from the K fragments in fr; the accumulator starts at minus
     // the row's reference, so the result is the exponent phase 2 needs.
-    static __device__ __forceinline__ f32x16 scores(const Row& r, const Frags& fr, const u32x4 (&qf)[NKS])
+    // `between(m)` runs behind MFMA m of the phase (a copy request, or nothing).
+    template <class F>
+    static __device__ __forceinline__ f32x16 scores(const Row& r, const Frags& fr, const u32x4 (&qf)[NKS], F&& between)
     {
         f32x16 S = mfma32(fr.kf[0], qf[0], USE_CNEG ? r.Cneg : zero16());
+        between(0);
 #pragma unroll
-        for (int ks = 1; ks < NKS; ++ks) S = mfma32(fr.kf[ks], qf[ks], S);
+        for (int ks = 1; ks < NKS; ++ks) {
+            S = mfma32(fr.kf[ks], qf[ks], S);
+            between(ks);
+        }
         return S;
     }
     // Phase 3 (Eq. (3)) of one block from the V^T fragments in fr and the row's exponentials.
-    static __device__ __forceinline__ void weighted_sum(Row& r, const Frags& fr)
+    template <class F>
+    static __device__ __forceinline__ void weighted_sum(Row& r, const Frags& fr, F&& between)
     {
 #pragma unroll
         for (int hf = 0; hf < 2; ++hf)
 #pragma unroll
-            for (int db = 0; db < NDB; ++db) r.O[db] = mfma32(fr.vf[hf][db], r.P[hf], r.O[db]);
+            for (int db = 0; db < NDB; ++db) {
+                r.O[db] = mfma32(fr.vf[hf][db], r.P[hf], r.O[db]);
+                between(NKS + hf * NDB + db);
+            }
     }
 
     // A score beyond the slack (or the first finite score of a row): move the reference to the
@@ -166,9 +180,13 @@ struct Pipe {
     template <bool SHIFT>
     static __device__ __forceinline__ void exponentials(Row& r, float delta)
     {
-        typedef __bf16 bf16x2 __attribute__((ext_vector_type(2)));
-        const unsigned ones = 0x3f803f80u;  // (1, 1) in bf16
-        float psum = r.l;
+        // The row sum is taken with plain additions of the unrounded exponentials.  A v_dot2c on
+        // the rounded pairs would be half the instructions, but dot instructions do not run beside
+        // the matrix pipe: each one waits until the MFMAs in flight on its SIMD have drained, from
+        // whichever wavefront they are, which serialises the vector phase with the matrix phase
+        // of the wavefront it shares the SIMD with (measured: an MFMA followed by one v_dot2c
+        // takes 51 cycles instead of 32; exponentials, conversions, max and fma add 1-3).
+        float psum0 = r.l, psum1 = 0.f;
 #pragma unroll
         for (int hf = 0; hf < 2; ++hf)
 #pragma unroll
@@ -176,13 +194,11 @@ struct Pipe {
                 const float s0 = r.S[8 * hf + 2 * w], s1 = r.S[8 * hf + 2 * w + 1];
                 const float p0 = __builtin_amdgcn_exp2f(SHIFT ? s0 - delta : s0);
                 const float p1 = __builtin_amdgcn_exp2f(SHIFT ? s1 - delta : s1);
-                const unsigned pk = pack_bf16(p0, p1);
-                r.P[hf][w] = pk;
-                // the row sum takes the rounded weights, the ones phase 3 multiplies with
-                psum = __builtin_amdgcn_fdot2_f32_bf16(__builtin_bit_cast(bf16x2, pk), __builtin_bit_cast(bf16x2, ones),
-                                                       psum, false);
+                r.P[hf][w] = pack_bf16(p0, p1);
+                psum0 += p0;
+                psum1 += p1;
             }
-        r.l = psum;
+        r.l = psum0 + psum1;
     }
 };
 
@@ -229,6 +245,8 @@ void attn_pipe_kernel(Problem pb, CountCfg cc, const bf16_t* __restrict__ q, con
 #pragma unroll
     for (int hf = 0; hf < 2; ++hf) voff[hf] = T::K_BYTES + ln * (BC * 2) + swz<BC * 2>(2 * hf + g, ln) * 16;
 
+    const __amdgpu_buffer_rsrc_t k_rsrc = __builtin_amdgcn_make_buffer_rsrc((void*)kh, 0, -1, 0x00020000);
+    const __amdgpu_buffer_rsrc_t v_rsrc = __builtin_amdgcn_make_buffer_rsrc((void*)vh, 0, -1, 0x00020000);
     const unsigned k_lane_off = dma_lane_offset<T::KROWB>(wave, lane);
     const unsigned v_lane_off = dma_lane_offset<BC * 2>(wave, lane);
 
@@ -340,27 +358,61 @@ void attn_pipe_kernel(Problem pb, CountCfg cc, const bf16_t* __restrict__ q, con
 #pragma unroll
             for (int ks = 0; ks < NKS; ++ks) qf[ks] = *(const u32x4*)(qh + (size_t)i * DK + ks * 16 + g * 8);
 
+            // Piece c (K pieces first) of the tile with K at byte ksoff and V^T at byte vsoff of the
+            // head, into the stage at LDS byte `stage`.  A buffer load: descriptor base, the lane's
+            // offset inside its piece, a scalar offset for tile and piece; no vector instruction.
+            auto issue_piece = [&](int c, int ksoff, int vsoff, unsigned stage) {
+                if (c < T::KPIECES) {
+                    const int m = wave + c * WAVES;
+                    __builtin_amdgcn_raw_ptr_buffer_load_lds(
+                        k_rsrc, (__attribute__((address_space(3))) void*)(lds + stage + m * 1024), 16,
+                        (int)k_lane_off, ksoff + m * 1024, 0, 0);
+                } else {
+                    const int m = wave + (c - T::KPIECES) * WAVES;
+                    __builtin_amdgcn_raw_ptr_buffer_load_lds(
+                        v_rsrc, (__attribute__((address_space(3))) void*)(lds + stage + T::K_BYTES + m * 1024), 16,
+                        (int)v_lane_off, vsoff + m * 1024, 0, 0);
+                }
+            };
             auto issue_tile = [&](int u) {
                 const int J = tile_of_step(u);
-                unsigned char* base = lds + (u % T::STAGES) * T::STAGE;
-                dma_pieces<T::KPIECES>(kh + (size_t)J * T::K_BYTES, base, k_lane_off, wave, WAVES);
-                dma_pieces<T::VPIECES>(vh + (size_t)J * T::V_BYTES, base + T::K_BYTES, v_lane_off, wave, WAVES);
+                const unsigned stage = (unsigned)(u % T::STAGES) * T::STAGE;
+#pragma unroll
+                for (int c = 0; c < T::PPW; ++c) issue_piece(c, J * T::K_BYTES, J * T::V_BYTES, stage);
             };
+            // A tile whose pieces this wavefront still has to request (SPREAD): set by the barrier
+            // that frees the stage, worked off by the two matrix phases that follow it.
+            bool req_on = false;
+            int req_k = 0, req_v = 0;
+            unsigned req_stage = 0;
             // Start of tile t: tiles t and t+1 are in LDS, every wavefront is done with tile t-1,
-            // whose stage takes tile t+STAGES-1.
-            auto tile_sync = [&](int t) {
-                // tiles t+2 .. t+STAGES-2 may stay in flight
-                if (T::STAGES > 3 && t + 2 < nT) __builtin_amdgcn_s_waitcnt(0x0F70 | ((T::STAGES - 3) * T::PPW));
+            // whose stage takes tile t+STAGES-1 (`defer`: by and by, see above).
+            auto tile_sync = [&](int t, bool defer) {
+                // tiles t+2 .. t+STAGES-2 may stay in flight, as far as the walk has them
+                const int ahead = nT - 2 - t;
+                if (T::STAGES > 4 && ahead >= 2) __builtin_amdgcn_s_waitcnt(0x0F70 | (2 * T::PPW));
+                else if (T::STAGES > 3 && ahead >= 1) __builtin_amdgcn_s_waitcnt(0x0F70 | T::PPW);
                 else __builtin_amdgcn_s_waitcnt(0x0F70);  // vmcnt(0)
                 __builtin_amdgcn_s_waitcnt(0xC07F);       // lgkmcnt(0): this wavefront's LDS reads are done
                 __builtin_amdgcn_s_barrier();
-                if (t + T::STAGES - 1 < nT) issue_tile(t + T::STAGES - 1);
+                const int u = t + T::STAGES - 1;
+                if (u < nT) {
+                    if (T::SPREAD && defer) {
+                        const int J = tile_of_step(u);
+                        req_on = true;
+                        req_k = J * T::K_BYTES;
+                        req_v = J * T::V_BYTES;
+                        req_stage = (unsigned)(u % T::STAGES) * T::STAGE;
+                    } else {
+                        issue_tile(u);
+                    }
+                }
             };
             // prologue of the ring: the first STAGES-1 tiles requested, tiles 0 and 1 awaited
             {
                 const int pre = nT < T::STAGES - 1 ? nT : T::STAGES - 1;
                 for (int u = 0; u < pre; ++u) issue_tile(u);
-                tile_sync(0);
+                tile_sync(0, false);
             }
             // The barrier of tile t (t >= 1) lies in front of E(2t) for group 0 and between E(2t) and
             // M(2t) for group 1.  A wavefront that joins the walk at block n_first first passes the
@@ -368,7 +420,7 @@ void attn_pipe_kernel(Problem pb, CountCfg cc, const bf16_t* __restrict__ q, con
             int next_sync = 1;
             {
                 const int upto = grp == 0 ? (n_first >> 1) : ((n_first - 1) >> 1);  // n_first == 0: none
-                for (; next_sync <= upto && next_sync < nT; ++next_sync) tile_sync(next_sync);
+                for (; next_sync <= upto && next_sync < nT; ++next_sync) tile_sync(next_sync, false);
             }
 
             if (n_first < NB) {
@@ -382,7 +434,7 @@ void attn_pipe_kernel(Problem pb, CountCfg cc, const bf16_t* __restrict__ q, con
                 {
                     const unsigned char* kblk = lds + stg + (1 - (n_first & 1)) * 32 * T::KROWB;
                     T::read_k(fr, kblk, koff);
-                    r.S = T::scores(r, fr, qf);
+                    r.S = T::scores(r, fr, qf, [](int) {});
                 }
                 int lim_base = len - 1;  // the lane's last allowed key
                 if (CAUSAL) lim_base = lim_base < i ? lim_base : i;
@@ -409,13 +461,35 @@ void attn_pipe_kernel(Problem pb, CountCfg cc, const bf16_t* __restrict__ q, con
                         else T::template exponentials<false>(r, 0.f);
                     }
                 };
-                auto phase_m = [&]() {
+                // M(n).  HALF: 0 / 1 for the first / second matrix phase behind a tile's barrier, which
+                // request the first / second half of the pending tile's pieces, each behind an
+                // MFMA of its own (a run of requests stalls on the queue of the address unit, and
+                // every wavefront of the workgroup would issue its run at the same moment); -1: none.
+                auto phase_m = [&](auto half) {
+                    constexpr int HALF = decltype(half)::value;
+                    constexpr int NMF = NKS + 2 * NDB;
+                    constexpr int PER = T::PPW / 2;
+                    auto between = [&](int m) {
+                        if constexpr (HALF >= 0 && T::SPREAD) {
+#pragma unroll
+                            for (int j = 0; j < PER; ++j)
+                                if (m == 1 + j * (NMF / PER)) {
+                                    __builtin_amdgcn_sched_barrier(0);
+                                    if (req_on) issue_piece(HALF * PER + j, req_k, req_v, req_stage);
+                                    __builtin_amdgcn_sched_barrier(0);
+                                }
+                        }
+                    };
                     __builtin_amdgcn_s_setprio(1);
-                    r.S = T::scores(r, fr, qf);  // first, so that E(n+1) finds them done; after the last
-                                                 // block: of stale keys, unused
-                    T::weighted_sum(r, fr);
+                    r.S = T::scores(r, fr, qf, between);  // first, so that E(n+1) finds them done; after
+                                                          // the last block: of stale keys, unused
+                    T::weighted_sum(r, fr, between);
                     __builtin_amdgcn_s_setprio(0);
+                    if (HALF == 1) req_on = false;
                 };
+                const std::integral_constant<int, 0> first_m{};
+                const std::integral_constant<int, 1> second_m{};
+                const std::integral_constant<int, -1> plain_m{};
                 auto next_tile = [&]() {
                     ++t;
                     stg = stg_n;
@@ -426,12 +500,12 @@ void attn_pipe_kernel(Problem pb, CountCfg cc, const bf16_t* __restrict__ q, con
 #pragma nounroll
                     while (t < t_end) {
                         const int J = masked ? tile_of_step(t) : 0;
-                        if (grp == 0 && t >= next_sync) { tile_sync(t); ++next_sync; }
+                        if (grp == 0 && t >= next_sync) { tile_sync(t, true); ++next_sync; }
                         phase_e(std::integral_constant<int, 1>{}, masked, J);
-                        if (grp == 1 && t >= next_sync) { tile_sync(t); ++next_sync; }
-                        phase_m();
+                        if (grp == 1 && t >= next_sync) { tile_sync(t, true); ++next_sync; }
+                        phase_m(first_m);
                         phase_e(std::integral_constant<int, 0>{}, masked, J);
-                        phase_m();
+                        phase_m(second_m);
                         next_tile();
                     }
                 };
@@ -439,7 +513,7 @@ void attn_pipe_kernel(Problem pb, CountCfg cc, const bf16_t* __restrict__ q, con
                 if (n_first & 1) {
                     const bool masked = n_first < n_edge_end;
                     phase_e(std::integral_constant<int, 0>{}, masked, masked ? tile_of_step(t) : 0);
-                    phase_m();
+                    phase_m(plain_m);
                     next_tile();
                 }
                 const int t_edge_end = (n_edge_end + 1) >> 1;  // tiles that hold an edge block: pair tests
@@ -447,7 +521,7 @@ void attn_pipe_kernel(Problem pb, CountCfg cc, const bf16_t* __restrict__ q, con
                 run_tiles(nT, false);
             }
             // keep the ring going to its end (wavefronts that never joined the walk)
-            for (; next_sync < nT; ++next_sync) tile_sync(next_sync);
+            for (; next_sync < nT; ++next_sync) tile_sync(next_sync, false);
             __builtin_amdgcn_s_waitcnt(0xC07F);
             __builtin_amdgcn_s_barrier();  // the next pass refills the stages
         }
