@@ -109,10 +109,17 @@ struct Pipe {
 #pragma unroll
         for (int e = 0; e < 16; ++e) S[e] = (8 * (e >> 2) + (e & 3)) <= lim ? S[e] : -INFINITY;
     }
-    static __device__ __forceinline__ void read_k(Frags& fr, const unsigned char* kblk, const int (&koff)[NKS])
+    // The chunk of k-step ks is chunk 2*ks + g XOR-ed with row bits, and 2*ks has no bit in
+    // common with g: the lane's byte address for k-step ks is its address for k-step 0 XOR 32*ks
+    // (32-key blocks start at multiples of 256 bytes).  ka0: LDS byte offset for k-step 0.
+    static __device__ __forceinline__ u32x4 read_k1(const unsigned char* lds, unsigned ka0, int ks)
+    {
+        return *(const u32x4*)(lds + (ka0 ^ (unsigned)(32 * ks)));
+    }
+    static __device__ __forceinline__ void read_k(Frags& fr, const unsigned char* lds, unsigned ka0)
     {
 #pragma unroll
-        for (int ks = 0; ks < NKS; ++ks) fr.kf[ks] = *(const u32x4*)(kblk + koff[ks]);
+        for (int ks = 0; ks < NKS; ++ks) fr.kf[ks] = read_k1(lds, ka0, ks);
     }
     static __device__ __forceinline__ void read_v(Frags& fr, const unsigned char* vstage, int voff0, int voff1)
     {
@@ -169,16 +176,21 @@ struct Pipe {
 #pragma unroll
             for (int e = 0; e < 16; ++e) r.O[db][e] *= alpha;
         if (USE_CNEG) {
+            // the scores at hand were taken against the old reference
 #pragma unroll
-            for (int e = 0; e < 16; ++e) r.Cneg[e] = -r.mref;
+            for (int e = 0; e < 16; ++e) {
+                r.Cneg[e] = -r.mref;
+                r.S[e] -= delta;
+            }
         }
         return delta;
     }
 
     // Phase 2 (Eq. (2)) of the block in r.S; the row sum is normalised at the very end.
     // SHIFT: the scores still refer to a reference that was `delta` lower.
-    template <bool SHIFT>
-    static __device__ __forceinline__ void exponentials(Row& r, float delta)
+    // `between(p)` runs behind score pair p (0..7): the LDS requests for the matrix phase.
+    template <bool SHIFT, class F>
+    static __device__ __forceinline__ void exponentials(Row& r, float delta, F&& between)
     {
         // The row sum is taken with plain additions of the unrounded exponentials.  A v_dot2c on
         // the rounded pairs would be half the instructions, but dot instructions do not run beside
@@ -197,6 +209,7 @@ struct Pipe {
                 r.P[hf][w] = pack_bf16(p0, p1);
                 psum0 += p0;
                 psum1 += p1;
+                between(4 * hf + w);
             }
         r.l = psum0 + psum1;
     }
@@ -239,9 +252,8 @@ void attn_pipe_kernel(Problem pb, CountCfg cc, const bf16_t* __restrict__ q, con
     // Swizzled LDS byte offsets of this lane's operand reads: K rows relative to the first row of
     // a 32-key block, V^T relative to the stage for the lower 32 keys of a tile (the upper 32 keys
     // lie 4 chunks further, which under the XOR swizzle is the offset XOR 64).
-    int koff[NKS], voff[2];
-#pragma unroll
-    for (int ks = 0; ks < NKS; ++ks) koff[ks] = ln * T::KROWB + swz<T::KROWB>(2 * ks + g, ln) * 16;
+    int voff[2];
+    const int koff0 = ln * T::KROWB + swz<T::KROWB>(g, ln) * 16;
 #pragma unroll
     for (int hf = 0; hf < 2; ++hf) voff[hf] = T::K_BYTES + ln * (BC * 2) + swz<BC * 2>(2 * hf + g, ln) * 16;
 
@@ -432,8 +444,7 @@ void attn_pipe_kernel(Problem pb, CountCfg cc, const bf16_t* __restrict__ q, con
                 unsigned stg_n = stg + T::STAGE == RING ? 0u : stg + T::STAGE;
                 // scores of the first block, outside the rotation
                 {
-                    const unsigned char* kblk = lds + stg + (1 - (n_first & 1)) * 32 * T::KROWB;
-                    T::read_k(fr, kblk, koff);
+                    T::read_k(fr, lds, stg + (1 - (n_first & 1)) * 32 * T::KROWB + koff0);
                     r.S = T::scores(r, fr, qf, [](int) {});
                 }
                 int lim_base = len - 1;  // the lane's last allowed key
@@ -446,20 +457,32 @@ void attn_pipe_kernel(Problem pb, CountCfg cc, const bf16_t* __restrict__ q, con
                     constexpr int UPPER = decltype(upper)::value;
                     if (masked) T::mask_block(r.S, lim_base - (J * BC + 32 * UPPER));
                     const float mxl = T::USE_CNEG ? T::max16(r.S) : T::max16(r.S) - r.mref;
-                    float delta = 0.f;
-                    const bool raised = __builtin_amdgcn_ballot_w64(mxl > r.thr) != 0ull;
-                    if (raised) delta = T::raise_reference(r, mxl);
-                    // requests first: V^T of this block; K of the next block, which is the lower half of
-                    // this tile or the upper half of the next tile
-                    T::read_v(fr, lds + stg, voff[0] ^ (64 * UPPER), voff[1] ^ (64 * UPPER));
-                    T::read_k(fr, UPPER ? lds + stg : lds + stg_n + 32 * T::KROWB, koff);
-                    __builtin_amdgcn_sched_barrier(0);
-                    if constexpr (!T::USE_CNEG) {
-                        T::template exponentials<true>(r, r.mref);
-                    } else {
-                        if (raised) T::template exponentials<true>(r, delta);
-                        else T::template exponentials<false>(r, 0.f);
-                    }
+                    if (__builtin_amdgcn_ballot_w64(mxl > r.thr) != 0ull) T::raise_reference(r, mxl);
+                    // The LDS requests for M(n) go out between the exponentials, a quarter of them
+                    // behind every second pair: K of the next block (the lower half of this tile or
+                    // the upper half of the next tile), which M(n) takes first, and V^T of this block.
+                    // In one run they queue up behind those of the other wavefronts and hold this one.
+                    const unsigned ka0 = (UPPER ? stg : stg_n + 32 * T::KROWB) + koff0;
+                    const unsigned char* vstage = lds + stg;
+                    const int voff0 = voff[0] ^ (64 * UPPER), voff1 = voff[1] ^ (64 * UPPER);
+                    auto reads = [&](int p) {
+                        if ((p & 1) == 0) return;
+                        const int q = p >> 1;  // 0..3
+                        __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+                        for (int u = 0; u < NKS / 4; ++u) fr.kf[q * (NKS / 4) + u] = T::read_k1(lds, ka0, q * (NKS / 4) + u);
+#pragma unroll
+                        for (int u = 0; u < (2 * NDB) / 4; ++u) {
+                            const int e = q * ((2 * NDB) / 4) + u, hf = e / NDB, db = e % NDB;
+                            fr.vf[hf][db] = *(const u32x4*)(vstage + (hf ? voff1 : voff0) + db * 32 * (BC * 2));
+                        }
+                        __builtin_amdgcn_sched_barrier(0);
+                    };
+                    if constexpr (!T::USE_CNEG) T::template exponentials<true>(r, r.mref, reads);
+                    else T::template exponentials<false>(r, 0.f, reads);
+                    // The weights are wanted here: without a use at this point the compiler sinks the
+                    // exponentials into the matrix phase, down to the block of their first MFMA.
+                    asm volatile("" : "+v"(r.P[0]), "+v"(r.P[1]), "+v"(r.l));
                 };
                 // M(n).  HALF: 0 / 1 for the first / second matrix phase behind a tile's barrier, which
                 // request the first / second half of the pending tile's pieces, each behind an
@@ -480,6 +503,7 @@ void attn_pipe_kernel(Problem pb, CountCfg cc, const bf16_t* __restrict__ q, con
                                 }
                         }
                     };
+                    __builtin_amdgcn_sched_barrier(0);  // the vector phase stays in front of the matrix phase
                     __builtin_amdgcn_s_setprio(1);
                     r.S = T::scores(r, fr, qf, between);  // first, so that E(n+1) finds them done; after
                                                           // the last block: of stale keys, unused
