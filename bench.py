@@ -30,9 +30,9 @@ MFMA_BF16_PEAK_TFLOPS = 2500.0   # MI355X dense bf16, published
 # HBM/fabric bytes per launch from rocprofv3 counter runs (FETCH_SIZE + WRITE_SIZE, each scaled by what
 # the same counter reads for a plain 1 GiB device copy: x2.00 and x1.00; see profiles/).  They hold for
 # the kernel sources with the hash below; with other sources the bench line carries null.
-TRAFFIC_SOURCES_SHA256 = "5eea66425a3956545c41448c1225704cb088685bf408555e86cac4969b22c196"
+TRAFFIC_SOURCES_SHA256 = "3c986876da2a75ab13cc65b766fce2d5f1a2f1329a1a0645209ff531c63a8e92"
 TRAFFIC_BYTES = {
-    "long": {"projection": int((2 * 590300 + 196600) * 1024), "attention": int((2 * 189700 + 106800) * 1024)},
+    "long": {"projection": int((2 * 590000 + 196600) * 1024), "attention": int((2 * 173300 + 97540) * 1024)},
 }
 
 
