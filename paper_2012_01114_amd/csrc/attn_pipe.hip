@@ -559,6 +559,13 @@ void attn_pipe_kernel(Problem pb, CountCfg cc, const bf16_t* __restrict__ q, con
             const float l_tot = r.l + __shfl_xor(r.l, 32, 64);
             const float inv = l_tot > 0.f ? 1.f / l_tot : 0.f;
             unsigned char* stage = lds + wave * (32 * DK * 2);
+            // The addresses below depend on the lane only.  Computed from an opaque copy of the lane
+            // number they stay here; otherwise the compiler hoists them out of the pass loop, spills
+            // them, and reloads them one by one between the stores, and every reload then waits
+            // (vmcnt) until the store before it has been acknowledged by memory.
+            int le = lane;
+            asm volatile("" : "+v"(le));
+            const int ln_e = le & 31, g_e = le >> 5;
 #pragma unroll
             for (int db = 0; db < NDB; ++db)
 #pragma unroll
@@ -567,13 +574,13 @@ void attn_pipe_kernel(Problem pb, CountCfg cc, const bf16_t* __restrict__ q, con
                     w[0] = pack_bf16(r.O[db][4 * r4 + 0] * inv, r.O[db][4 * r4 + 1] * inv);
                     w[1] = pack_bf16(r.O[db][4 * r4 + 2] * inv, r.O[db][4 * r4 + 3] * inv);
                     const int c = 4 * db + r4;
-                    *(u32x2*)(stage + ln * (DK * 2) + ((c ^ (ln & (CPR - 1))) << 4) + 8 * g) = w;
+                    *(u32x2*)(stage + ln_e * (DK * 2) + ((c ^ (ln_e & (CPR - 1))) << 4) + 8 * g_e) = w;
                 }
             __builtin_amdgcn_s_waitcnt(0xC07F);  // lgkmcnt(0): only this wavefront reads what it wrote
             bf16_t* obase = out + ((size_t)bb * N + i0w) * ((size_t)pb.H * DK) + (size_t)h * DK;
 #pragma unroll
             for (int it = 0; it < 32 * CPR / 64; ++it) {
-                const int row = it * (64 / CPR) + lane / CPR, c = lane % CPR;
+                const int row = it * (64 / CPR) + le / CPR, c = le % CPR;
                 const u32x4 v = *(const u32x4*)(stage + row * (DK * 2) + ((c ^ (row & (CPR - 1))) << 4));
                 if (i0w + row < N) *(u32x4*)(obase + (size_t)row * ((size_t)pb.H * DK) + c * 8) = v;
             }
