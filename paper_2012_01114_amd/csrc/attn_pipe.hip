@@ -14,10 +14,11 @@
 //
 // Schedule.  The walk is cut into 32-key blocks; for block n a wavefront runs
 //     E(n)  vector ALUs :  pair tests of an edge block, P(n) = exp2(S(n) - ref), row sums
-//                          (phase 2, Eq. (2)); first of all it requests from LDS the
-//                          fragments M(n) will take: V^T of block n, K of block n+1
-//     M(n)  matrix cores:  O += V(n)^T.P(n)^T (phase 3, Eq. (3)),
-//                          S(n+1) = K(n+1).Q^T (phase 1 of the next block, Eq. (1))
+//                          (phase 2, Eq. (2)); between the exponentials it requests from
+//                          LDS the fragments M(n) will take: K of block n+1, V^T of block n
+//     M(n)  matrix cores:  S(n+1) = K(n+1).Q^T (phase 1 of the next block, Eq. (1)),
+//                          O += V(n)^T.P(n)^T (phase 3, Eq. (3)); the copy requests for a
+//                          later tile go out behind single MFMAs
 // in the order E(n), M(n), E(n+1), ...  A workgroup of eight wavefronts has two
 // groups of four; wavefronts w and w+4 share a SIMD.  Group 0 meets the per-tile
 // workgroup barrier in front of E(2t), group 1 between E(2t) and M(2t): after
@@ -31,14 +32,14 @@
 // scale*log2(e) and the score MFMAs start from minus the row's reference, so the
 // MFMA yields the base-2 exponent itself and an exponential costs one v_exp_f32;
 // row sums are plain fp32 additions (dot instructions stall on the matrix pipe).
-// The reference is raised only when a score exceeds it by more than 2^RAISE (rare after the first blocks); until then
-// exponentials may reach 2^RAISE, which fp32 sums and bf16 operands hold without
-// loss.  Raising rescales the row at the head of E(n), when everything computed
+// The reference is raised only when a score exceeds it by more than 2^RAISE (rare
+// after the first blocks); until then exponentials may reach 2^RAISE, which fp32
+// sums and bf16 operands hold without loss.  Raising rescales the row at the head of E(n), when everything computed
 // with the old reference has been added to O.
 //
 // K[64][d] and V^T[d][64] tiles go from global memory straight into a ring of
-// LDS stages (global_load_lds, 16 bytes per lane) ahead of their use; one
-// workgroup barrier per tile.  LDS rows are unpadded; their 16-byte chunks are
+// LDS stages (buffer_load ... lds, 16 bytes per lane) two to three tiles ahead of
+// their use; one workgroup barrier per tile.  LDS rows are unpadded; their 16-byte chunks are
 // XOR-swizzled with the row index (conflict-free 128-bit reads).
 #include <type_traits>
 
