@@ -136,7 +136,14 @@ struct Pipe {
     template <class F>
     static __device__ __forceinline__ f32x16 scores(const Row& r, const Frags& fr, const u32x4 (&qf)[NKS], F&& between)
     {
-        f32x16 S = mfma32(fr.kf[0], qf[0], USE_CNEG ? r.Cneg : zero16());
+        f32x16 S;
+        if constexpr (USE_CNEG) {
+            // D and C in different registers: written with the builtin, the compiler copies the 16
+            // registers of C first and accumulates in place.
+            asm volatile("v_mfma_f32_32x32x16_bf16 %0, %1, %2, %3" : "=&v"(S) : "v"(fr.kf[0]), "v"(qf[0]), "v"(r.Cneg));
+        } else {
+            S = mfma32(fr.kf[0], qf[0], zero16());
+        }
         between(0);
 #pragma unroll
         for (int ks = 1; ks < NKS; ++ks) {
