@@ -1,5 +1,5 @@
 // Helpers shared by the fused attention kernels: tile counting, LDS swizzle and
-// the global-to-LDS copy of K / V^T tiles.
+// the lane offsets of the global-to-LDS copy of K / V^T tiles.
 #pragma once
 
 #include "mfma_common.h"
@@ -36,7 +36,7 @@ __device__ __forceinline__ int swz(int chunk, int row)
 // fetches the chunk that belongs there under the swizzle.  With the pieces of a
 // wavefront 4 or 8 apart, the lane's byte offset inside its piece does not depend
 // on the piece, so it is computed once (dma_lane_offset) and every copy is a
-// uniform base address plus that offset.
+// uniform base (buffer descriptor and scalar offset) plus that offset.
 template <int ROWB>
 __device__ __forceinline__ unsigned dma_lane_offset(int first, int lane)
 {
@@ -45,18 +45,6 @@ __device__ __forceinline__ unsigned dma_lane_offset(int first, int lane)
     const int rl = lane / CPR, p = lane % CPR;
     const int row = first * RPP + rl;
     return (unsigned)(rl * ROWB + swz<ROWB>(p, row) * 16);
-}
-template <int COUNT>
-__device__ __forceinline__ void dma_pieces(const unsigned char* __restrict__ gsrc, unsigned char* ldst,
-                                           unsigned lane_off, int first, int step)
-{
-#pragma unroll
-    for (int u = 0; u < COUNT; ++u) {
-        const int m = first + u * step;
-        __builtin_amdgcn_global_load_lds(
-            (const __attribute__((address_space(1))) void*)(gsrc + (size_t)m * 1024 + lane_off),
-            (__attribute__((address_space(3))) void*)(ldst + m * 1024), 16, 0, 0);
-    }
 }
 
 }  // namespace attnring

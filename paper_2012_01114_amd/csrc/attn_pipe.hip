@@ -122,14 +122,6 @@ struct Pipe {
 #pragma unroll
         for (int ks = 0; ks < NKS; ++ks) fr.kf[ks] = read_k1(lds, ka0, ks);
     }
-    static __device__ __forceinline__ void read_v(Frags& fr, const unsigned char* vstage, int voff0, int voff1)
-    {
-#pragma unroll
-        for (int db = 0; db < NDB; ++db) {
-            fr.vf[0][db] = *(const u32x4*)(vstage + voff0 + db * 32 * (BC * 2));
-            fr.vf[1][db] = *(const u32x4*)(vstage + voff1 + db * 32 * (BC * 2));
-        }
-    }
     // Phase 1 (Eq. (1)) of one block from the K fragments in fr; the accumulator starts at minus
     // the row's reference, so the result is the exponent phase 2 needs.
     // `between(m)` runs behind MFMA m of the phase (a copy request, or nothing).

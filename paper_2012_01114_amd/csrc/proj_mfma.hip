@@ -304,7 +304,7 @@ __global__ __launch_bounds__(256) void proj_mfma_kernel(int Bsz, int N, int Npad
 
 // ---------------------------------------------------------------------------
 // The GEMM for d_model a multiple of 64 and 16-byte aligned weights, with the operands
-// copied from global memory straight into LDS (global_load_lds, 16 bytes per lane) and
+// copied from global memory straight into LDS (buffer_load ... lds, 16 bytes per lane) and
 // the weights taken in the caller's layout.
 //
 // A request for 64 KiB of operands takes longer to come back than the MFMAs of one
