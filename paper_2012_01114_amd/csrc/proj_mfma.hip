@@ -308,16 +308,17 @@ __global__ __launch_bounds__(256) void proj_mfma_kernel(int Bsz, int N, int Npad
 // the weights taken in the caller's layout.
 //
 // A request for 64 KiB of operands takes longer to come back than the MFMAs of one
-// 64-deep slice take to run, so two slices have to be in flight.  LDS cannot hold
-// three 64-deep stages of a 256 x 256 tile; it holds five 32-deep ones.  They form a
-// ring of slots; a slice is requested as two half slices into the two slots that the
-// half slices four and five behind it have left, which gives a request one and a half
-// slice periods to land.  A slot holds the x side as BT rows of 64 bytes (32 k of a
-// vector), its four 16-byte chunks XOR-swizzled with bits 2..3 of the row index,
-// which keeps the 128-bit operand reads of 16 consecutive rows on distinct banks, and
-// the weight side as it lies in memory, 32 k-rows of BT columns, read with the
-// transposing LDS read (see the offset tables in the kernel).  WR x WC wavefronts
-// share a BT x BT tile.
+// 64-deep slice take to run, so two slices have to be in flight, and LDS cannot hold
+// three 64-deep stages of a 256 x 256 tile.  The two sides are kept in rings of their own:
+//   x side   three units of BT rows x 128 bytes (64 k of a vector: a whole slice).  The vector
+//            cache works by 128-byte lines, and a request that takes 64 bytes from each of 16
+//            rows costs it twice the lines of one that takes 8 whole ones.  A unit is free when
+//            its slice is done; its 16-byte chunks are XOR-swizzled with bits 1..3 of the row
+//            index (128-bit operand reads of 16 consecutive rows fall on distinct banks).
+//   weights  four slots of 32 k-rows x BT columns (half a slice) as they lie in memory, read
+//            with the transposing LDS read (see the offset table in the kernel).  A slot is
+//            free half a slice after its first read.
+// Every request has at least one slice period to land.  WR x WC wavefronts share a BT x BT tile.
 // ---------------------------------------------------------------------------
 template <int BT, int WR, int WC>
 __global__ __launch_bounds__(64 * WR * WC, (WR * WC) / 4 * (BT == 256 ? 1 : 2))
@@ -330,16 +331,18 @@ void proj_dma_kernel(int Bsz, int N, int Npad, int D, int H, int d, const bf16_t
     constexpr int NW = WR * WC;
     constexpr int TA = BT / WR, TB = BT / WC;    // wavefront tile: TA rows of the A side, TB of the B side
     constexpr int NA = TA / 32, NBK = TB / 32;   // MFMA blocks per edge
-    constexpr int SIDE = BT * 64;                // bytes of one operand side per slot
-    constexpr int SLOT = 2 * SIDE;
-    constexpr int NSLOT = 5;
-    constexpr int PPW = (BT / 16) / NW;          // 1 KiB pieces (16 rows) per wavefront, side and slot
-    constexpr int PER_SLICE = 4 * PPW;           // requests of one wavefront per 64-deep slice
-    static_assert(PPW >= 1 && PER_SLICE <= 15, "piece count fits the wavefront count and the vmcnt field");
+    constexpr int XU = BT * 128;                 // bytes of one x unit: BT rows x 64 k
+    constexpr int NXU = 3;
     constexpr int WROWB = BT * 2;                // bytes of one k-row of the weight side in a slot
-    constexpr int WCPR = WROWB / 16;             // its 16-byte chunks
+    constexpr int WS = 32 * WROWB;               // bytes of one weight slot: 32 k-rows
+    constexpr int NWS = 4;
+    constexpr int W_BASE = NXU * XU;
+    constexpr int XPW = (BT / 8) / NW;           // x pieces (1 KiB: 8 rows x 128 bytes) per wavefront and slice
+    constexpr int WPW = (WS / 1024) / NW;        // weight pieces (1 KiB) per wavefront and half slice
+    static_assert(XPW == 4 && WPW == 2, "the request schedule below deals 4 + 2 + 2 requests per slice");
+    constexpr int WCPR = WROWB / 16;             // 16-byte chunks of a weight k-row
     constexpr int WRPP = 64 / WCPR;              // k-rows per 1 KiB piece
-    __shared__ __attribute__((aligned(1024))) unsigned char lds[NSLOT * SLOT];
+    __shared__ __attribute__((aligned(1024))) unsigned char lds[NXU * XU + NWS * WS];
     clear_counters(counters);  // this is the first kernel of a forward pass on this path
 
     const int tid = threadIdx.x;
@@ -369,53 +372,49 @@ void proj_dma_kernel(int Bsz, int N, int Npad, int D, int H, int d, const bf16_t
 
     // Source byte offsets of this lane for its pieces.  32 bits hold them (attn_init bounds the
     // element counts), which lets a request take a uniform 64-bit base and this offset.
-    //   x side: rows are vectors, 64 bytes (32 k) each; piece m = wave + NW*u holds rows
-    //           16m..16m+15; the lane lands at row 16m + lane/4, chunk position lane%4;
+    //   x side: rows are vectors, 128 bytes (64 k) each; piece m = wave + NW*u holds rows
+    //           8m..8m+7; the lane lands at row 8m + lane/8, chunk position lane%8;
     //   w side: rows are k, BT columns each; piece m holds k-rows m*WRPP..; the lane lands at
     //           k-row m*WRPP + lane/WCPR, chunk position lane%WCPR.
     // Either way it fetches the chunk that the swizzle of its row puts at that position.
-    unsigned xoff[PPW], woff[PPW];
+    unsigned xoff[XPW], woff[WPW];
 #pragma unroll
-    for (int u = 0; u < PPW; ++u) {
-        const int row = (wave + NW * u) * 16 + (lane >> 2);
-        const int c = (lane & 3) ^ ((row >> 2) & 3);
+    for (int u = 0; u < XPW; ++u) {
+        const int row = (wave + NW * u) * 8 + (lane >> 3);
+        const int c = (lane & 7) ^ ((row >> 1) & 7);
         const int xr = x0 + row;
         const int bb = xr / Npad;
         int i = xr - bb * Npad;
         i = i < N ? i : N - 1;
         xoff[u] = 2u * ((unsigned)(bb * N + i) * (unsigned)D + c * 8);
+    }
+#pragma unroll
+    for (int u = 0; u < WPW; ++u) {
         const int kr = (wave + NW * u) * WRPP + lane / WCPR;
         const int wc16 = (lane % WCPR) ^ (4 * (kr & 3));
         woff[u] = 2u * ((unsigned)kr * (unsigned)HD + wc16 * 8);
     }
-    const int x_side = is_v ? 0 : SIDE, w_side = is_v ? SIDE : 0;
-    // Request number q (0 .. PER_SLICE-1) of the slice that starts at k0: piece u = q/4, operand
-    // q/2%2, half q%2 (the two halves of an x row share a cache line and are requested back to
-    // back).  The first half of the slice goes into slot s0, the second into slot s1.
     // Buffer addressing: descriptor base + the lane's 32-bit offset + a scalar offset for the
     // slice, so that a request costs no vector instruction for its address.
     const __amdgpu_buffer_rsrc_t x_rsrc = __builtin_amdgcn_make_buffer_rsrc((void*)X, 0, -1, 0x00020000);
     const __amdgpu_buffer_rsrc_t w_rsrc = __builtin_amdgcn_make_buffer_rsrc((void*)Wm, 0, -1, 0x00020000);
-    auto request = [&](int q, int k0, int s0, int s1) {
-        const int u = q >> 2, w_op = (q >> 1) & 1, h = q & 1;
-        const int m = wave + NW * u;
-        unsigned char* dst = lds + (h ? s1 : s0) * SLOT + m * 1024 + (w_op ? w_side : x_side);
-        const unsigned kk = (unsigned)(k0 + 32 * h);
-        if (w_op)
-            __builtin_amdgcn_raw_ptr_buffer_load_lds(w_rsrc, (__attribute__((address_space(3))) void*)dst, 16,
-                                                     (int)woff[u], (int)(2u * kk * (unsigned)HD), 0, 0);
-        else
-            __builtin_amdgcn_raw_ptr_buffer_load_lds(x_rsrc, (__attribute__((address_space(3))) void*)dst, 16,
-                                                     (int)xoff[u], (int)(2u * kk), 0, 0);
+    // piece u of the x side of the slice that starts at k0, into unit `unit`
+    auto req_x = [&](int u, int k0, int unit) {
+        unsigned char* dst = lds + unit * XU + (wave + NW * u) * 1024;
+        __builtin_amdgcn_raw_ptr_buffer_load_lds(x_rsrc, (__attribute__((address_space(3))) void*)dst, 16,
+                                                 (int)xoff[u], (int)(2u * (unsigned)k0), 0, 0);
     };
-    auto issue = [&](int k0, int s0, int s1) {
-#pragma unroll
-        for (int q = 0; q < PER_SLICE; ++q) request(q, k0, s0, s1);
+    // piece u of half h of the weight side of the slice that starts at k0, into slot `slot`
+    auto req_w = [&](int u, int k0, int h, int slot) {
+        unsigned char* dst = lds + W_BASE + slot * WS + (wave + NW * u) * 1024;
+        __builtin_amdgcn_raw_ptr_buffer_load_lds(w_rsrc, (__attribute__((address_space(3))) void*)dst, 16,
+                                                 (int)woff[u], (int)(2u * (unsigned)(k0 + 32 * h) * (unsigned)HD), 0, 0);
     };
 
-    // LDS byte offsets of this lane's operand reads for the two k-steps of a slot, from the slot
-    // base, for the first 32-row block of the wavefront's share of each side.
-    //   x side: 128 bits = 8 k of row ln, chunk 2*ks + g.
+    // LDS byte offsets of this lane's operand reads, from the unit / slot base, for the first
+    // 32-row block of the wavefront's share of each side.
+    //   x side: 128 bits = 8 k of row ln, chunk 2*ks + g of the four k-steps of a slice; 2*ks has no
+    //           bit in common with g, so the offset for k-step ks is the one for k-step 0 XOR 32*ks.
     //   w side: stored k-major, read with the transposing 64-bit LDS read: 16 lanes hand in the
     //           addresses of a 4 (k) x 16 (columns) patch, four columns each, and lane i gets
     //           column i of the patch, its four k values.  Lanes 16..31 take the next 16 columns,
@@ -428,17 +427,14 @@ void proj_dma_kernel(int Bsz, int N, int Npad, int D, int H, int d, const bf16_t
     const int x_row0 = is_v ? wr * TA : wc * TB;  // first x row / first w column of this wavefront
     const int w_col0 = is_v ? wc * TB : wr * TA;
     constexpr int NWB = NA > NBK ? NA : NBK;  // 32-column blocks of the weight side of a wavefront
-    int xfo[2], wfo[NWB];  // w side: k-step 0, first read; the others lie whole k-rows further (same k % 4)
-#pragma unroll
-    for (int ks = 0; ks < 2; ++ks) {
-        xfo[ks] = x_side + (x_row0 + ln) * 64 + (((2 * ks + g) ^ ((ln >> 2) & 3)) << 4);
-    }
+    int wfo[NWB];  // w side: k-step 0, first read; the others lie whole k-rows further (same k % 4)
+    const int xfo0 = (x_row0 + ln) * 128 + ((g ^ ((ln >> 1) & 7)) << 4);  // x_row0 is a multiple of 32
 #pragma unroll
     for (int blk = 0; blk < NWB; ++blk) {
         const int i16 = lane & 15;
         const int k = 8 * g + (i16 >> 2);
         const int col = w_col0 + 32 * blk + 16 * ((lane >> 4) & 1) + 4 * (i16 & 3);
-        wfo[blk] = w_side + k * WROWB + (((col >> 3) ^ (4 * (k & 3))) << 4) + ((col & 7) << 1);
+        wfo[blk] = k * WROWB + (((col >> 3) ^ (4 * (k & 3))) << 4) + ((col & 7) << 1);
     }
 
     f32x16 acc[NA][NBK];
@@ -457,8 +453,9 @@ void proj_dma_kernel(int Bsz, int N, int Npad, int D, int H, int d, const bf16_t
     // would drain.  The order is pinned with scheduling fences; the group-barrier solver drops its
     // pattern as soon as memory requests are part of it.
     u32x4 af[2][NA], bf[2][NBK];
-    auto x_frag = [&](const unsigned char* slot_base, int ks, int blk) -> u32x4 {
-        return *(const u32x4*)(slot_base + xfo[ks] + blk * 2048);
+    // ks4: k-step of the slice, 0..3
+    auto x_frag = [&](const unsigned char* unit_base, int ks4, int blk) -> u32x4 {
+        return *(const u32x4*)(unit_base + (xfo0 ^ (32 * ks4)) + blk * 4096);
     };
     // The transposing reads are written out by hand: as a builtin, the compiler takes them to
     // alias the copies into LDS that are still in flight and makes each of them wait for all of
@@ -474,27 +471,31 @@ void proj_dma_kernel(int Bsz, int N, int Npad, int D, int H, int d, const bf16_t
     };
     // fragment number r of a k-step, in the order a0, b0.., a1..; the weights are the A side of q and
     // k tiles and the B side of v tiles
-    auto read_frag = [&](auto is_v_, u32x4 (&fa)[NA], u32x4 (&fb)[NBK], int r, const unsigned char* slot_base,
-                         int ks) {
+    // hs: half slice 0 / 1 of x unit `unit` and weight slot `slot`; ks: k-step 0 / 1 of the half slice
+    auto read_frag = [&](auto is_v_, u32x4 (&fa)[NA], u32x4 (&fb)[NBK], int r, const unsigned char* unit_base,
+                         const unsigned char* slot_base, int hs, int ks) {
         constexpr bool IS_V = decltype(is_v_)::value;
         if (r == 0 || r > NBK) {
             const int a = r == 0 ? 0 : r - NBK;
-            fa[a] = IS_V ? x_frag(slot_base, ks, a) : w_frag(slot_base, ks, a);
+            fa[a] = IS_V ? x_frag(unit_base, 2 * hs + ks, a) : w_frag(slot_base, ks, a);
         } else {
-            fb[r - 1] = IS_V ? w_frag(slot_base, ks, r - 1) : x_frag(slot_base, ks, r - 1);
+            fb[r - 1] = IS_V ? w_frag(slot_base, ks, r - 1) : x_frag(unit_base, 2 * hs + ks, r - 1);
         }
     };
-    auto load_frags = [&](auto is_v_, u32x4 (&fa)[NA], u32x4 (&fb)[NBK], int slot, int ks) {
+    auto load_frags = [&](auto is_v_, u32x4 (&fa)[NA], u32x4 (&fb)[NBK], int unit, int slot, int hs, int ks) {
 #pragma unroll
-        for (int r = 0; r < NA + NBK; ++r) read_frag(is_v_, fa, fb, r, lds + slot * SLOT, ks);
+        for (int r = 0; r < NA + NBK; ++r)
+            read_frag(is_v_, fa, fb, r, lds + unit * XU, lds + W_BASE + slot * WS, hs, ks);
     };
+    // `reqs(i)`, i = 0 .. ND-1: the requests that go out behind the MFMAs of this k-step
     auto kstep = [&](auto is_v_, const u32x4 (&fa)[NA], const u32x4 (&fb)[NBK], u32x4 (&na)[NA], u32x4 (&nb)[NBK],
-                     int slot, int ks, auto nd_, int q0, int k0, int s0, int s1) {
+                     int unit, int slot, int hs, int ks, auto nd_, auto&& reqs) {
         constexpr int ND = decltype(nd_)::value;
         constexpr int NRD = NA + NBK, NMF = NA * NBK;
         static_assert(NRD % 2 == 0 && NRD / 2 <= NMF, "read pairs fit behind the MFMAs of a k-step");
         static_assert(ND <= NMF, "at most one request per MFMA");
-        const unsigned char* slot_base = lds + slot * SLOT;
+        const unsigned char* unit_base = lds + unit * XU;
+        const unsigned char* slot_base = lds + W_BASE + slot * WS;
         __builtin_amdgcn_sched_barrier(0);
         __builtin_amdgcn_s_waitcnt(0xC07F);  // lgkmcnt(0): the fragments of this k-step are in
         __builtin_amdgcn_sched_barrier(0);
@@ -505,55 +506,96 @@ void proj_dma_kernel(int Bsz, int N, int Npad, int D, int H, int d, const bf16_t
                 acc[a][b] = mfma32(fa[a], fb[b], acc[a][b]);
                 const int m = a * NBK + b + 1;  // MFMAs issued so far
                 if (m <= NRD / 2) {
-                    read_frag(is_v_, na, nb, 2 * m - 2, slot_base, ks);
-                    read_frag(is_v_, na, nb, 2 * m - 1, slot_base, ks);
+                    read_frag(is_v_, na, nb, 2 * m - 2, unit_base, slot_base, hs, ks);
+                    read_frag(is_v_, na, nb, 2 * m - 1, unit_base, slot_base, hs, ks);
                 }
-                if (ND > 0 && (m * ND) % NMF == 0) request(q0 + m * ND / NMF - 1, k0, s0, s1);
+                if (ND > 0 && (m * ND) % NMF == 0) reqs(m * ND / NMF - 1);
                 __builtin_amdgcn_sched_barrier(0);
             }
     };
-    auto next_slot = [](int s) { return s + 1 >= NSLOT ? s + 1 - NSLOT : s + 1; };
     constexpr std::integral_constant<int, 0> no_req{};
+    constexpr std::integral_constant<int, 1> one_req{};
+    constexpr std::integral_constant<int, 2> two_req{};
 
-    // Slice j: half slices in slots sa and its successor.  The barrier of a half slice sits before
-    // its second k-step, whose fragments are in registers by then: behind it the slot is free, and
-    // the first fragments of the next half slice are read while the second k-step's MFMAs run, so
-    // the matrix pipe has work on both sides of the barrier.  With `more`, slice j+2 is requested
-    // behind the first barrier, into the slot that the half slice before this one left and into sa.
-    auto slice = [&](auto is_v_, auto more_, int j, int sa) {
-        constexpr bool MORE = decltype(more_)::value;
-        constexpr std::integral_constant<int, MORE ? PER_SLICE / 2 : 0> nreq{};
-        const int sb = next_slot(sa), sc = next_slot(sb), se = next_slot(next_slot(sc));
-        const int k2 = (j + 2) * 64;
-        kstep(is_v_, af[0], bf[0], af[1], bf[1], sa, 1, no_req, 0, 0, 0, 0);
-        __builtin_amdgcn_s_waitcnt(0xC07F);  // lgkmcnt(0)
+    // Slice j: x in unit ux, its two weight half slices in slots wa and wa+1.  A k-step runs the
+    // MFMAs of fragments that are in registers and reads those of the next k-step.  The barrier
+    // of a half slice sits before its second k-step, whose fragments are in registers by then:
+    // behind the first barrier (A) slot wa is free, behind the second (B) slot wa+1 and unit ux,
+    // and the matrix pipe has work on both sides of either.  Each k-step sends two requests for
+    // what has just become free, the weight piece first:
+    //     step 1   weights (j+1, half 1) piece 1  -> slot wa+3      x (j+2) piece 0 -> unit ux+2
+    //     step 2   weights (j+2, half 0) piece 0  -> slot wa        x (j+2) piece 1
+    //     step 3   weights (j+2, half 0) piece 1  -> slot wa        x (j+2) piece 2
+    //     step 4   weights (j+2, half 1) piece 0  -> slot wa+1      x (j+2) piece 3
+    // Loads return in order.  Barrier B wants x (j+1) and the first weight half of slice j+1 in,
+    // whose last piece went out in step 4 of slice j-1: the six requests of steps 1-3 may be in
+    // flight.  Barrier A wants the second weight half of slice j in, whose last piece went out
+    // first in step 1 of slice j-1: nine requests may be in flight.  VAR: 2 if slice j+2 exists,
+    // 1 if slice j+1 is the last, 0 if slice j is.
+    auto slice = [&](auto is_v_, auto var_, int j, int& ux, int& wa) {
+        constexpr int VAR = decltype(var_)::value;
+        constexpr bool E1 = VAR >= 1, E2 = VAR == 2;
+        const int ux1 = ux == NXU - 1 ? 0 : ux + 1, ux2 = ux1 == NXU - 1 ? 0 : ux1 + 1;
+        const int wb = (wa + 1) & 3, wc = (wa + 2) & 3, wd = (wa + 3) & 3;
+        const int k1 = (j + 1) * 64, k2 = (j + 2) * 64;
+        kstep(is_v_, af[0], bf[0], af[1], bf[1], ux, wa, 0, 1, std::integral_constant<int, (E1 ? 1 : 0) + (E2 ? 1 : 0)>{},
+              [&](int i) {
+                  if (E1 && i == 0) req_w(1, k1, 1, wd);
+                  else req_x(0, k2, ux2);
+              });
+        __builtin_amdgcn_s_waitcnt(0x0070 | (8 * (E1 ? 1 : 0) + (E2 ? 1 : 0)));  // lgkmcnt(0), see above
         __builtin_amdgcn_s_barrier();
-        kstep(is_v_, af[1], bf[1], af[0], bf[0], sb, 0, nreq, 0, k2, se, sa);
-        kstep(is_v_, af[0], bf[0], af[1], bf[1], sb, 1, nreq, PER_SLICE / 2, k2, se, sa);
-        // lgkmcnt(0); slice j+1 has landed (loads return in order; slice j+2 may be in flight)
-        __builtin_amdgcn_s_waitcnt(0x0070 | (MORE ? PER_SLICE : 0));
+        kstep(is_v_, af[1], bf[1], af[0], bf[0], ux, wb, 1, 0, std::integral_constant<int, E2 ? 2 : 0>{}, [&](int i) {
+            if (i == 0) req_w(0, k2, 0, wa);
+            else req_x(1, k2, ux2);
+        });
+        kstep(is_v_, af[0], bf[0], af[1], bf[1], ux, wb, 1, 1, std::integral_constant<int, E2 ? 2 : 0>{}, [&](int i) {
+            if (i == 0) req_w(1, k2, 0, wa);
+            else req_x(2, k2, ux2);
+        });
+        __builtin_amdgcn_s_waitcnt(0x0070 | ((E1 ? 1 : 0) + 5 * (E2 ? 1 : 0)));
         __builtin_amdgcn_s_barrier();
-        kstep(is_v_, af[1], bf[1], af[0], bf[0], sc, 0, no_req, 0, 0, 0, 0);  // reads ahead into slice j+1
-        return sc;
+        // reads ahead into slice j+1
+        kstep(is_v_, af[1], bf[1], af[0], bf[0], ux1, wc, 0, 0, std::integral_constant<int, E2 ? 2 : 0>{}, [&](int i) {
+            if (i == 0) req_w(0, k2, 1, wb);
+            else req_x(3, k2, ux2);
+        });
+        ux = ux1;
+        wa = wc;
     };
 
+    // Prologue: slice 0 whole, and of slice 1 what steps 2-4 of a slice before slice 0 would
+    // have sent (its last weight piece follows in step 1 of slice 0).
     const int ns = D / 64;
-    issue(0, 0, 1);
+    req_w(0, 0, 0, 0);
+    req_w(1, 0, 0, 0);
+#pragma unroll
+    for (int u = 0; u < XPW; ++u) req_x(u, 0, 0);
+    req_w(0, 0, 1, 1);
+    req_w(1, 0, 1, 1);
     if (ns > 1) {
-        issue(64, 2, 3);
-        __builtin_amdgcn_s_waitcnt(0x0F70 | PER_SLICE);  // loads return in order: slice 0 has landed
+        req_x(0, 64, 1);
+        req_w(0, 64, 0, 2);
+        req_x(1, 64, 1);
+        req_w(1, 64, 0, 2);
+        req_x(2, 64, 1);
+        req_w(0, 64, 1, 3);
+        req_x(3, 64, 1);
+        __builtin_amdgcn_s_waitcnt(0x0F70 | 7);  // loads return in order: slice 0 has landed
     } else {
         __builtin_amdgcn_s_waitcnt(0x0F70);
     }
     __builtin_amdgcn_s_barrier();
     auto all_slices = [&](auto is_v_) {
-        load_frags(is_v_, af[0], bf[0], 0, 0);
-        int sa = 0;  // slot of the first half of slice j
+        load_frags(is_v_, af[0], bf[0], 0, 0, 0, 0);
+        int ux = 0, wa = 0;
         int j = 0;
 #pragma nounroll
-        for (; j + 2 < ns; ++j) sa = slice(is_v_, std::true_type{}, j, sa);
+        for (; j + 2 < ns; ++j) slice(is_v_, two_req, j, ux, wa);
 #pragma nounroll
-        for (; j < ns; ++j) sa = slice(is_v_, std::false_type{}, j, sa);
+        for (; j + 1 < ns; ++j) slice(is_v_, one_req, j, ux, wa);
+#pragma nounroll
+        for (; j < ns; ++j) slice(is_v_, no_req, j, ux, wa);
     };
     if (is_v) all_slices(std::true_type{});
     else all_slices(std::false_type{});
