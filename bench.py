@@ -30,9 +30,9 @@ MFMA_BF16_PEAK_TFLOPS = 2500.0   # MI355X dense bf16, published
 # HBM/fabric bytes per launch from rocprofv3 counter runs (FETCH_SIZE + WRITE_SIZE, each scaled by what
 # the same counter reads for a plain 1 GiB device copy: x2.00 and x1.00; see profiles/).  They hold for
 # the kernel sources with the hash below; with other sources the bench line carries null.
-TRAFFIC_SOURCES_SHA256 = "e177d4f217085dcafe51460d44396bcfc9267b58716c5638de73af4c54126849"
+TRAFFIC_SOURCES_SHA256 = "546f0d74889b621ae70ad800f561e9b216457a67cf189f036e7884f2293a9a5c"
 TRAFFIC_BYTES = {
-    "long": {"projection": int((2 * 590100 + 196600) * 1024), "attention": int((2 * 142400 + 65790) * 1024)},
+    "long": {"projection": int((2 * 590100 + 196600) * 1024), "attention": int((2 * 140100 + 65790) * 1024)},
 }
 
 
