@@ -394,6 +394,10 @@ void attn_pipe_kernel(Problem pb, CountCfg cc, const bf16_t* __restrict__ q, con
             };
             // A tile whose pieces this wavefront still has to request (SPREAD): set by the barrier
             // that frees the stage, worked off by the two matrix phases that follow it.
+            // LDS byte offsets of the stages of the walk's current tile and of the one after it,
+            // kept by increments
+            constexpr unsigned RING = T::STAGES * T::STAGE;
+            unsigned stg = 0, stg_n = 0;
             bool req_on = false;
             int req_k = 0, req_v = 0;
             unsigned req_stage = 0;
@@ -414,7 +418,7 @@ void attn_pipe_kernel(Problem pb, CountCfg cc, const bf16_t* __restrict__ q, con
                         req_on = true;
                         req_k = J * T::K_BYTES;
                         req_v = J * T::V_BYTES;
-                        req_stage = (unsigned)(u % T::STAGES) * T::STAGE;
+                        req_stage = stg == 0 ? RING - T::STAGE : stg - T::STAGE;  // the stage tile t-1 has left
                     } else {
                         issue_tile(u);
                     }
@@ -438,10 +442,8 @@ void attn_pipe_kernel(Problem pb, CountCfg cc, const bf16_t* __restrict__ q, con
             if (n_first < NB) {
                 typename T::Frags fr;
                 int t = n_first >> 1;
-                // LDS byte offsets of the stages of tile t and of tile t+1, kept by increments
-                constexpr unsigned RING = T::STAGES * T::STAGE;
-                unsigned stg = (unsigned)(t % T::STAGES) * T::STAGE;
-                unsigned stg_n = stg + T::STAGE == RING ? 0u : stg + T::STAGE;
+                stg = (unsigned)(t % T::STAGES) * T::STAGE;
+                stg_n = stg + T::STAGE == RING ? 0u : stg + T::STAGE;
                 // scores of the first block, outside the rotation
                 {
                     T::read_k(fr, lds, stg + (1 - (n_first & 1)) * 32 * T::KROWB + koff0);
