@@ -9,7 +9,10 @@ inputs already resident in HBM.  Prints ONE JSON line.
             wall time per step
   roofline  the dominant kernel (by time) against the bf16 MFMA peak; its
             duration is measured with HIP events recorded by the library on the
-            launch stream around every kernel of the timed steps
+            launch stream around every kernel, in a pass of its own after the
+            headline pass (which carries no events)
+  workloads the same three rates (whole call, projection, attention) for the
+            other workloads of the metric
   cpu_baseline  the float64 CPU checker timed on a bounded sample of the same
             workload (reported, not a target)
 """
@@ -93,12 +96,92 @@ def cpu_baseline(w, f64, lens, budget_s=12.0, max_heads=256, rows_too=False):
                       f"{min(256, w.n)} random query rows each; FLOPs counted for the sample only"}
 
 
+class Session:
+    """One workload resident on the GPU: inputs, context, output buffer."""
+
+    def __init__(self, name, tiles="auto", skip_padded_rows=False):
+        import torch
+        from paper_2012_01114_amd import attnring as ar
+        from paper_2012_01114_amd import inputs
+        self.ar, self.torch = ar, torch
+        self.w = w = inputs.WORKLOADS[name]
+        stored, self.f64 = inputs.make_inputs(w)
+        self.lens = stored["lens"]
+        dev = torch.device("cuda:0")
+        self.X, self.Wq, self.Wk, self.Wv = [stored[k].to(dev) for k in ("X", "Wq", "Wk", "Wv")]
+        self.lens_dev = None if self.lens is None else torch.from_numpy(self.lens).to(dev)
+        self.out = torch.empty(w.batch, w.n, w.hd, dtype=self.X.dtype, device=dev)
+        dt = ar.ATTN_F32 if w.dtype == "f32" else ar.ATTN_BF16
+        flags = {"auto": 0, "wide": ar.ATTN_FLAG_WIDE_TILES, "narrow": ar.ATTN_FLAG_NARROW_TILES}[tiles]
+        self.rows_too = skip_padded_rows and self.lens is not None
+        if self.rows_too:
+            flags |= ar.ATTN_FLAG_SKIP_PADDED_ROWS
+        self.ctx = ar.attn_init(w.batch, w.n, w.d_model, w.n_heads, w.d_k, w.p, dt, 0.0, flags)
+        ar.attn_set_key_lengths(self.ctx, self.lens_dev)
+        self.stream = torch.cuda.current_stream(dev)
+
+    def step(self):
+        self.ar.attn_forward(self.ctx, self.X, self.Wq, self.Wk, self.Wv, self.w.scheme, self.out, self.stream)
+
+    def flops(self):
+        """(attention FLOPs on needed pairs, projection FLOPs of the rows some allowed pair uses)."""
+        import numpy as np
+        w, lens = self.w, self.lens
+        pairs = needed_pairs(w, lens, self.rows_too)
+        kv_rows = w.batch * w.n if lens is None else int(np.minimum(np.maximum(lens, 0), w.n).sum())
+        q_rows = kv_rows if self.rows_too else w.batch * w.n
+        return 4.0 * w.d_k * pairs, 2.0 * (q_rows + 2 * kv_rows) * w.d_model * w.hd, pairs
+
+    def measure(self, steps, warmup, repeats):
+        """Headline pass: `repeats` timed regions of exactly `steps` back-to-back calls each, wall clock
+        between device synchronisations, nothing else on the stream; the median region counts.
+        Then a separate pass of `steps` calls with the library's per-kernel HIP events switched on."""
+        torch, ar = self.torch, self.ar
+        for _ in range(warmup):
+            self.step()
+        torch.cuda.synchronize()
+        regions = []
+        for _ in range(repeats):
+            torch.cuda.synchronize()
+            t0 = time.perf_counter()
+            for _ in range(steps):
+                self.step()
+            torch.cuda.synchronize()
+            regions.append((time.perf_counter() - t0) * 1e3 / steps)
+        ar.attn_profile(self.ctx, True)
+        for _ in range(steps):
+            self.step()
+        prof = ar.attn_profile_read(self.ctx)
+        ar.attn_profile(self.ctx, False)
+        stats = ar.attn_stats(self.ctx)
+        regions_sorted = sorted(regions)
+        return regions_sorted[len(regions) // 2], regions, prof, stats
+
+    def close(self):
+        self.torch.cuda.synchronize()
+        self.ar.attn_destroy(self.ctx)
+        self.ctx = None
+
+
+def rates(attn_flop, proj_flop, ms_step, prof):
+    """Whole call, projection alone, attention alone: TFLOP/s and share of the bf16 MFMA peak."""
+    def one(flop, ms):
+        t = flop / (ms * 1e-3) / 1e12
+        return {"ms": round(ms, 4), "tflops": round(t, 2), "pct_of_peak": round(100.0 * t / MFMA_BF16_PEAK_TFLOPS, 2)}
+    return {"whole_call": one(attn_flop + proj_flop, ms_step),
+            "projection": one(proj_flop, prof["ms_projection"]),
+            "attention": one(attn_flop, prof["ms_attention"])}
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
-    ap.add_argument("--steps", type=int, default=50)
+    ap.add_argument("--steps", type=int, default=100)
     ap.add_argument("--warmup", type=int, default=10)
+    ap.add_argument("--repeats", type=int, default=5, help="timed regions of --steps calls each; the median counts")
     ap.add_argument("--workload", default="long", help="tiny|encoder|causal|long|padded")
+    ap.add_argument("--others", default="causal,encoder,padded",
+                    help="workloads timed besides the headline one (GPU only, reported under `workloads`); '' for none")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--skip-padded-rows", action="store_true",
                     help="padded workload: leave the padded vectors out as queries too (ATTN_FLAG_SKIP_PADDED_ROWS); "
@@ -121,7 +204,6 @@ def main():
     if args.gpus != 1:
         sys.exit("bench.py: this build runs on one GPU only (no collectives, no sharding); use --gpus 1")
 
-    import numpy as np
     import torch
     from paper_2012_01114_amd import attnring as ar
     from paper_2012_01114_amd import inputs
@@ -131,47 +213,15 @@ def main():
     if not os.path.exists(ar.LIB_PATH):
         from paper_2012_01114_amd import build as libbuild
         libbuild.build()
-    w = inputs.WORKLOADS[args.workload]
-    stored, f64 = inputs.make_inputs(w)
-    lens = stored["lens"]
-    dev = torch.device("cuda:0")
-    X, Wq, Wk, Wv = [stored[k].to(dev) for k in ("X", "Wq", "Wk", "Wv")]
-    lens_dev = None if lens is None else torch.from_numpy(lens).to(dev)
-    out = torch.empty(w.batch, w.n, w.hd, dtype=X.dtype, device=dev)
-    dt = ar.ATTN_F32 if w.dtype == "f32" else ar.ATTN_BF16
-    flags = {"auto": 0, "wide": ar.ATTN_FLAG_WIDE_TILES, "narrow": ar.ATTN_FLAG_NARROW_TILES}[args.tiles]
-    rows_too = args.skip_padded_rows and lens is not None
-    if rows_too:
-        flags |= ar.ATTN_FLAG_SKIP_PADDED_ROWS
-    ctx = ar.attn_init(w.batch, w.n, w.d_model, w.n_heads, w.d_k, w.p, dt, 0.0, flags)
-    ar.attn_set_key_lengths(ctx, lens_dev)
-    stream = torch.cuda.current_stream(dev)
 
-    for _ in range(args.warmup):
-        ar.attn_forward(ctx, X, Wq, Wk, Wv, w.scheme, out, stream)
-    torch.cuda.synchronize()
-
-    # timed region: exactly K steps; the library records HIP events around each kernel
-    ar.attn_profile(ctx, True)
-    torch.cuda.synchronize()
-    t0 = time.perf_counter()
-    for _ in range(args.steps):
-        ar.attn_forward(ctx, X, Wq, Wk, Wv, w.scheme, out, stream)
-    torch.cuda.synchronize()
-    t1 = time.perf_counter()
-    prof = ar.attn_profile_read(ctx)
-    ar.attn_profile(ctx, False)
-    stats = ar.attn_stats(ctx)
-
-    ms_step = (t1 - t0) * 1e3 / args.steps
-    pairs = needed_pairs(w, lens, rows_too)
+    ses = Session(args.workload, args.tiles, args.skip_padded_rows)
+    w, lens, rows_too = ses.w, ses.lens, ses.rows_too
+    ms_step, regions, prof, stats = ses.measure(args.steps, args.warmup, args.repeats)
+    attn_flop, proj_flop, pairs = ses.flops()
     assert pairs == stats["pairs_needed"][0], (pairs, stats["pairs_needed"])
-    attn_flop = 4.0 * w.d_k * pairs
-    # projection: every q row, and the k and v rows that some allowed pair uses (those below the key length)
-    kv_rows = w.batch * w.n if lens is None else int(np.minimum(np.maximum(lens, 0), w.n).sum())
-    q_rows = kv_rows if rows_too else w.batch * w.n
-    proj_flop = 2.0 * (q_rows + 2 * kv_rows) * w.d_model * w.hd
     value = (attn_flop + proj_flop) / (ms_step * 1e-3) / 1e12
+    f64 = ses.f64
+    ses.close()
 
     kern = {
         "attention": {"flop": attn_flop, "ms": prof["ms_attention"]},
@@ -190,22 +240,45 @@ def main():
              for k, v in kern.items()}
     extra["prepare_avg_ms"] = round(prof["ms_prepare"], 4)
 
+    def describe(w, lens, rows_too):
+        return (f"{w.name}: batch {w.batch}, n {w.n}, d_model {w.d_model}, heads {w.n_heads}, "
+                f"d_k {w.d_k}, scheme {inputs.SCHEME_NAMES[w.scheme]}, P {w.p}"
+                + (", key lengths from seed" if lens is not None else "")
+                + (", padded rows left out" if rows_too else ""))
+
     line = {
         "metric": METRIC, "value": round(value, 2), "unit": "TFLOP/s", "n_gpus": 1, "steps": args.steps,
         "warmup": args.warmup, "ms_per_step": round(ms_step, 4), "higher_is_better": True, "scaling": "weak",
         "vs_baseline": None, "dtype": "bf16" if w.dtype == "bf16" else "f32", "data": "synthetic",
         "pct_bf16_mfma_peak": round(100.0 * value / MFMA_BF16_PEAK_TFLOPS, 2),
-        "config": {"workload": f"{w.name}: batch {w.batch}, n {w.n}, d_model {w.d_model}, heads {w.n_heads}, "
-                               f"d_k {w.d_k}, scheme {inputs.SCHEME_NAMES[w.scheme]}, P {w.p}"
-                               + (", key lengths from seed" if lens is not None else "")
-                               + (", padded rows left out" if rows_too else ""),
+        "timing": {"repeats": args.repeats, "ms_per_step_each": [round(r, 4) for r in regions],
+                   "reported": "median region; per-kernel times from a separate pass with HIP events"},
+        "operands": "projection: bf16 x bf16 -> fp32; q, k, v and the exponentials kept in fp16 (same MFMA rate), "
+                    "scores and weighted sums accumulate in fp32; out rounded to bf16",
+        "config": {"workload": describe(w, lens, rows_too),
                    "needed_pairs": pairs, "full_pairs": stats["pairs_full"],
                    "tiles_executed": stats["tiles_executed"], "tiles_full": stats["tiles_full"]},
         "roofline": roofline,
         "kernels": extra,
     }
-    torch.cuda.synchronize()
-    ar.attn_destroy(ctx)
+
+    # the other workloads of the metric: GPU only, same protocol, inputs drawn once each
+    others = {}
+    for name in [n for n in args.others.split(",") if n and n != args.workload]:
+        o = Session(name)
+        o_ms, o_regions, o_prof, o_stats = o.measure(args.steps, args.warmup, args.repeats)
+        o_attn, o_proj, o_pairs = o.flops()
+        assert o_pairs == o_stats["pairs_needed"][0]
+        rec = rates(o_attn, o_proj, o_ms, o_prof)
+        rec["ms_per_step"] = round(o_ms, 4)
+        rec["workload"] = describe(o.w, o.lens, False)
+        others[name] = rec
+        o.close()
+        del o
+        torch.cuda.empty_cache()
+    if others:
+        line["workloads"] = others
+
     if not args.no_cpu_baseline:
         line["cpu_baseline"] = cpu_baseline(w, f64, lens, rows_too=rows_too)
     print(json.dumps(line))

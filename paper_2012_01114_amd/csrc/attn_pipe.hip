@@ -1,4 +1,4 @@
-// Fused phases 1-3 (Sec. 3.1, Eq. (1)-(3)) on the bf16 matrix cores of gfx950,
+// Fused phases 1-3 (Sec. 3.1, Eq. (1)-(3)) on the 16-bit matrix cores of gfx950,
 // FULL and masked scheme, scheduled so that the two wavefronts that share a SIMD
 // keep its matrix cores and its vector ALUs busy at the same time.
 //
@@ -25,7 +25,7 @@
 // every barrier one group is in a vector phase while the other is in a matrix
 // phase, and they stay half an iteration apart.  Scores are computed transposed
 // (S^T = K.Q^T): a lane holds 16 keys of ONE query per 32x32 block, the
-// exponentials, rounded to bf16, are already in B-operand layout for
+// exponentials, rounded to half precision, are already in B-operand layout for
 // O^T += V^T.P^T, and a row needs no cross-lane traffic on the common path.
 //
 // Online softmax with a lazily raised reference.  q arrives pre-multiplied by
@@ -34,7 +34,7 @@
 // row sums are plain fp32 additions (dot instructions stall on the matrix pipe).
 // The reference is raised only when a score exceeds it by more than 2^RAISE (rare
 // after the first blocks); until then exponentials may reach 2^RAISE, which fp32
-// sums and bf16 operands hold without loss.  Raising rescales the row at the head of E(n), when everything computed
+// sums and half-precision operands hold without loss.  Raising rescales the row at the head of E(n), when everything computed
 // with the old reference has been added to O.
 //
 // K[64][d] and V^T[d][64] tiles go from global memory straight into a ring of
@@ -78,7 +78,7 @@ struct Pipe {
         f32x16 O[NDB];  // O^T, un-normalised
         f32x16 S;       // base-2 scores, minus the reference, of the block whose phase 2 comes next
         f32x16 Cneg;    // minus the reference: the C operand the score MFMAs start from
-        u32x4 P[2];     // exponentials of the current block, bf16, B-operand layout
+        u32x4 P[2];     // exponentials of the current block, half precision, B-operand layout
         float thr;      // RAISE once the row has a reference, -inf before
         float mref;     // the reference (0 before the row has one)
         float l;        // this lane's part of the row sum
@@ -132,14 +132,14 @@ struct Pipe {
         if constexpr (USE_CNEG) {
             // D and C in different registers: written with the builtin, the compiler copies the 16
             // registers of C first and accumulates in place.
-            asm volatile("v_mfma_f32_32x32x16_bf16 %0, %1, %2, %3" : "=&v"(S) : "v"(fr.kf[0]), "v"(qf[0]), "v"(r.Cneg));
+            asm volatile("v_mfma_f32_32x32x16_f16 %0, %1, %2, %3" : "=&v"(S) : "v"(fr.kf[0]), "v"(qf[0]), "v"(r.Cneg));
         } else {
-            S = mfma32(fr.kf[0], qf[0], zero16());
+            S = mfma32h(fr.kf[0], qf[0], zero16());
         }
         between(0);
 #pragma unroll
         for (int ks = 1; ks < NKS; ++ks) {
-            S = mfma32(fr.kf[ks], qf[ks], S);
+            S = mfma32h(fr.kf[ks], qf[ks], S);
             between(ks);
         }
         return S;
@@ -152,7 +152,7 @@ struct Pipe {
         for (int hf = 0; hf < 2; ++hf)
 #pragma unroll
             for (int db = 0; db < NDB; ++db) {
-                r.O[db] = mfma32(fr.vf[hf][db], r.P[hf], r.O[db]);
+                r.O[db] = mfma32h(fr.vf[hf][db], r.P[hf], r.O[db]);
                 between(NKS + hf * NDB + db);
             }
     }
@@ -206,7 +206,7 @@ struct Pipe {
                 const float s0 = r.S[8 * hf + 2 * w], s1 = r.S[8 * hf + 2 * w + 1];
                 const float p0 = __builtin_amdgcn_exp2f(SHIFT ? s0 - delta : s0);
                 const float p1 = __builtin_amdgcn_exp2f(SHIFT ? s1 - delta : s1);
-                r.P[hf][w] = pack_bf16(p0, p1);
+                r.P[hf][w] = pack_f16(p0, p1);
                 psum0 += p0;
                 psum1 += p1;
                 between(4 * hf + w);
@@ -218,8 +218,8 @@ struct Pipe {
 template <int DK, int WAVES, bool CAUSAL>
 __global__ __launch_bounds__(64 * WAVES)
 __attribute__((amdgpu_waves_per_eu(Pipe<DK, WAVES, CAUSAL>::OCC, Pipe<DK, WAVES, CAUSAL>::OCC)))
-void attn_pipe_kernel(Problem pb, CountCfg cc, const bf16_t* __restrict__ q, const bf16_t* __restrict__ k,
-                      const bf16_t* __restrict__ vt, bf16_t* __restrict__ out, int n_qtiles, int per_head, int n_work)
+void attn_pipe_kernel(Problem pb, CountCfg cc, const h16_t* __restrict__ q, const h16_t* __restrict__ k,
+                      const h16_t* __restrict__ vt, bf16_t* __restrict__ out, int n_qtiles, int per_head, int n_work)
 {
     typedef Pipe<DK, WAVES, CAUSAL> T;
     constexpr int NKS = T::NKS, NDB = T::NDB, BR = T::BR;
@@ -245,7 +245,7 @@ void attn_pipe_kernel(Problem pb, CountCfg cc, const bf16_t* __restrict__ q, con
     const int rlen = pb.skip_rows ? len : N;  // query rows at or past it take part in no pair
     const int nkt_all = Npad / BC;
 
-    const bf16_t* qh = q + (size_t)bh * Npad * DK;
+    const h16_t* qh = q + (size_t)bh * Npad * DK;
     const unsigned char* kh = (const unsigned char*)(k + (size_t)bh * Npad * DK);
     const unsigned char* vh = (const unsigned char*)(vt + (size_t)bh * Npad * DK);
 
@@ -604,7 +604,7 @@ void attn_pipe_kernel(Problem pb, CountCfg cc, const bf16_t* __restrict__ q, con
 
 }  // namespace
 
-hipError_t launch_attn_pipe(const Problem& pb, const bf16_t* q, const bf16_t* k, const bf16_t* vt, bf16_t* out,
+hipError_t launch_attn_pipe(const Problem& pb, const h16_t* q, const h16_t* k, const h16_t* vt, bf16_t* out,
                             int waves, hipStream_t s)
 {
     const bool causal = pb.scheme == SCHEME_CAUSAL;

@@ -19,13 +19,16 @@ struct attn_ctx {
     float scale;
     bool mfma_shape;  // shape and dtype fit the bf16 MFMA kernels
     // bf16 MFMA workspace
-    bf16_t *qb, *kb, *vtb, *wt;
+    h16_t *qb, *kb, *vtb;  // projected q, k, v^T, half precision
+    bf16_t* wt;
     // generic float workspace (allocated on first use)
     float *qf, *kf, *vf;
     float* scores;  // q = k = v scheme: one n x n score matrix per (batch, head)
     unsigned long long* counters;
     const int32_t* lens;
     // last forward
+    const int32_t* last_lens;  // the key lengths that call ran with
+    bool last_rows_too;
     hipStream_t last_stream;
     int last_scheme;
     int last_proj_gemms;
@@ -107,12 +110,20 @@ __global__ __launch_bounds__(1024) void sum_counters_kernel(unsigned long long* 
 
 attn_status ensure_generic_workspace(attn_ctx* c)
 {
-    if (c->qf) return ATTN_OK;
+    if (c->qf && c->kf && c->vf) return ATTN_OK;
     const size_t bytes = (size_t)c->cfg.batch * c->cfg.n_heads * c->cfg.n * c->cfg.d_k * sizeof(float);
     float** dst[3] = {&c->qf, &c->kf, &c->vf};
     for (auto p : dst) {
+        if (*p) continue;
         hipError_t e = hipMalloc((void**)p, bytes);
-        if (e != hipSuccess) return hip_fail(c, "hipMalloc(float q/k/v workspace)", e);
+        if (e != hipSuccess) {
+            // all three or none: a later call must not find a partial workspace
+            for (auto r : dst) {
+                if (*r) (void)hipFree(*r);
+                *r = nullptr;
+            }
+            return hip_fail(c, "hipMalloc(float q/k/v workspace)", e);
+        }
     }
     return ATTN_OK;
 }
@@ -125,8 +136,8 @@ attn_status sum_over_lengths(attn_ctx* c, F f, unsigned long long* out)
 {
     const int B = c->cfg.batch, N = c->cfg.n;
     std::vector<int32_t> lens((size_t)B, N);
-    if (c->lens) {
-        hipError_t e = hipMemcpy(lens.data(), c->lens, sizeof(int32_t) * (size_t)B, hipMemcpyDeviceToHost);
+    if (c->last_lens) {
+        hipError_t e = hipMemcpy(lens.data(), c->last_lens, sizeof(int32_t) * (size_t)B, hipMemcpyDeviceToHost);
         if (e != hipSuccess) return hip_fail(c, "hipMemcpy(key lengths)", e);
     }
     unsigned long long s = 0;
@@ -184,8 +195,8 @@ attn_status attn_init(const attn_config* cfg, attn_ctx** out_ctx)
     e = hipMalloc((void**)&c->counters, sizeof(unsigned long long) * CNT_BUFFER_WORDS);
     if (e == hipSuccess) e = hipMemset(c->counters, 0, sizeof(unsigned long long) * CNT_BUFFER_WORDS);
     if (e == hipSuccess && c->mfma_shape) {
-        const size_t qkv = (size_t)cfg->batch * c->Npad * hd * sizeof(bf16_t);
-        bf16_t** dst[3] = {&c->qb, &c->kb, &c->vtb};
+        const size_t qkv = (size_t)cfg->batch * c->Npad * hd * sizeof(h16_t);
+        h16_t** dst[3] = {&c->qb, &c->kb, &c->vtb};
         for (auto p : dst) {
             if (e == hipSuccess) e = hipMalloc((void**)p, qkv);
             if (e == hipSuccess) e = hipMemset(*p, 0, qkv);  // rows past n stay zero for good
@@ -331,6 +342,8 @@ attn_status attn_forward(attn_ctx* ctx, const void* X, const void* Wq, const voi
         ctx->prof_calls += 1;
     }
     ctx->last_stream = s;
+    ctx->last_lens = ctx->lens;
+    ctx->last_rows_too = pb.skip_rows;
     ctx->last_scheme = scheme;
     ctx->have_forward = true;
     return ATTN_OK;
@@ -358,7 +371,7 @@ attn_status attn_stats(attn_ctx* ctx, attn_stats_t* out)
     out->tiles_full = B * H * P * P;
     attn_status st = ATTN_OK;
     unsigned long long per_head_sum = 0;
-    const bool rows_too = (cf.flags & ATTN_FLAG_SKIP_PADDED_ROWS) != 0 && ctx->lens != nullptr;
+    const bool rows_too = ctx->last_rows_too;
     switch (ctx->last_scheme) {
     case ATTN_SCHEME_FULL:  // Sec. 3.2: n^2 per phase; with key padding n*len
         st = sum_over_lengths(ctx, [n, rows_too](unsigned long long L) { return (rows_too ? L : n) * L; },

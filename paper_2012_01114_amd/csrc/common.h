@@ -7,7 +7,8 @@
 
 namespace attnring {
 
-typedef unsigned short bf16_t;  // raw bfloat16 bits
+typedef unsigned short bf16_t;  // raw bfloat16 bits: the caller's X, W and out
+typedef unsigned short h16_t;   // raw half-precision bits: the projected q, k, v between the kernels
 
 enum { SCHEME_FULL = 0, SCHEME_SYMMETRIC = 1, SCHEME_CAUSAL = 2 };
 
@@ -48,7 +49,11 @@ hipError_t launch_attn_generic(const Problem& pb, const float* q, const float* k
                                void* out, hipStream_t s);
 hipError_t launch_sym_generic(const Problem& pb, const float* z, float* scores, void* out, hipStream_t s);
 
-// ---- bf16 MFMA path (d_k 64 or 128, FULL and CAUSAL) -----------------------
+// ---- matrix-core path (bf16 storage, d_k 64 or 128, FULL and CAUSAL) --------
+// The projection contracts bf16 operands; q, k, v leave it in half precision (fp32 accumulators
+// rounded once to an 11-bit significand instead of bfloat16's 8: with bfloat16 there, the roundings
+// of q, k and v alone reach 1.5e-2 on outputs of size 2, three quarters of the 2e-2 allowed) and the
+// attention kernel contracts half-precision operands, at the same matrix-core rate.
 // q, k: [B][H][Npad][d]; vt: [B][H][Npad/64][d][64] with the keys of every 16-group stored in MFMA
 // operand order.  Wt: [3][H*d][D], transposed weights, needed only when the projection cannot read
 // the weights in place (launch_transpose_w fills it, and is then the first kernel of the call).
@@ -56,10 +61,10 @@ hipError_t launch_transpose_w(const Problem& pb, const bf16_t* Wq, const bf16_t*
                               bf16_t* Wt, hipStream_t s);
 bool proj_reads_weights_in_place(const Problem& pb, const bf16_t* Wq, const bf16_t* Wk, const bf16_t* Wv);
 hipError_t launch_proj_mfma(const Problem& pb, const bf16_t* X, const bf16_t* Wq, const bf16_t* Wk,
-                            const bf16_t* Wv, const bf16_t* Wt, bf16_t* q, bf16_t* k, bf16_t* vt, hipStream_t s);
+                            const bf16_t* Wv, const bf16_t* Wt, h16_t* q, h16_t* k, h16_t* vt, hipStream_t s);
 // Fused phases 1-3 with redundant blocks left out; `waves` wavefronts of 32 rows per workgroup:
 // 4 or 8 for d_k = 64, 8 for d_k = 128.
-hipError_t launch_attn_pipe(const Problem& pb, const bf16_t* q, const bf16_t* k, const bf16_t* vt,
+hipError_t launch_attn_pipe(const Problem& pb, const h16_t* q, const h16_t* k, const h16_t* vt,
                             bf16_t* out, int waves, hipStream_t s);
 // Physical score-block edge of the MFMA attention kernels (phys_br = phys_bc).
 enum { MFMA_BLOCK = 32 };

@@ -1,7 +1,7 @@
 // q/k/v projections (Sec. 3.1: q, k, v are linear maps of the inputs x by three
 // learned matrices; one set per head) as ONE bf16 MFMA GEMM over the stacked
-// output columns [q | k | v], fp32 accumulation, written straight into the
-// layouts the attention kernel streams:
+// output columns [q | k | v], fp32 accumulation, rounded once to half precision and
+// written straight into the layouts the attention kernel streams:
 //   q, k : [B][H][Npad][d]            (row = vector, d contiguous)
 //   v^T  : [B][H][Npad/64][d][64]     (per 64-key block, key contiguous, and the
 //                                      keys of each 16-group in MFMA operand order)
@@ -151,8 +151,8 @@ __device__ __forceinline__ bool past_key_length(const int* __restrict__ lens, in
 template <int BT>
 __global__ __launch_bounds__(256) void proj_mfma_kernel(int Bsz, int N, int Npad, int D, int H, int d,
                                                         const bf16_t* __restrict__ X,
-                                                        const bf16_t* __restrict__ Wt, bf16_t* __restrict__ qo,
-                                                        bf16_t* __restrict__ ko, bf16_t* __restrict__ vto,
+                                                        const bf16_t* __restrict__ Wt, h16_t* __restrict__ qo,
+                                                        h16_t* __restrict__ ko, h16_t* __restrict__ vto,
                                                         int tiles_x, int tiles_w, float qscale, const int* __restrict__ lens, bool skip_q_rows)
 {
     constexpr int WT = BT / 2;          // wavefront tile edge
@@ -268,11 +268,11 @@ __global__ __launch_bounds__(256) void proj_mfma_kernel(int Bsz, int N, int Npad
                     const int which = col >= HD ? 1 : 0;
                     const int cc = col - which * HD;
                     const int h = cc / d, l = cc - h * d;
-                    bf16_t* dst = (which ? ko : qo) + (((size_t)bb * H + h) * Npad + i) * d + l;
+                    h16_t* dst = (which ? ko : qo) + (((size_t)bb * H + h) * Npad + i) * d + l;
                     const float qs = which ? 1.f : qscale;  // q is stored pre-multiplied (see launch_proj_mfma)
                     u32x2 w;
-                    w[0] = pack_bf16(acc[a][b][4 * r4 + 0] * qs, acc[a][b][4 * r4 + 1] * qs);
-                    w[1] = pack_bf16(acc[a][b][4 * r4 + 2] * qs, acc[a][b][4 * r4 + 3] * qs);
+                    w[0] = pack_f16_sat(acc[a][b][4 * r4 + 0] * qs, acc[a][b][4 * r4 + 1] * qs);
+                    w[1] = pack_f16_sat(acc[a][b][4 * r4 + 2] * qs, acc[a][b][4 * r4 + 3] * qs);
                     *(u32x2*)dst = w;
                 }
         }
@@ -292,10 +292,10 @@ __global__ __launch_bounds__(256) void proj_mfma_kernel(int Bsz, int N, int Npad
                     if (i >= N) continue;
                     const int blk = i >> 6, r64 = i & 63;
                     const int slot = (r64 & 48) | vt_slot16(r64 & 15);
-                    bf16_t* dst = vto + ((((size_t)bb * H + h) * (Npad >> 6) + blk) * d + l) * 64 + slot;
+                    h16_t* dst = vto + ((((size_t)bb * H + h) * (Npad >> 6) + blk) * d + l) * 64 + slot;
                     u32x2 w;
-                    w[0] = pack_bf16(acc[a][b][4 * r4 + 0], acc[a][b][4 * r4 + 1]);
-                    w[1] = pack_bf16(acc[a][b][4 * r4 + 2], acc[a][b][4 * r4 + 3]);
+                    w[0] = pack_f16_sat(acc[a][b][4 * r4 + 0], acc[a][b][4 * r4 + 1]);
+                    w[1] = pack_f16_sat(acc[a][b][4 * r4 + 2], acc[a][b][4 * r4 + 3]);
                     *(u32x2*)dst = w;
                 }
         }
@@ -324,7 +324,7 @@ template <int BT, int WR, int WC>
 __global__ __launch_bounds__(64 * WR * WC, (WR * WC) / 4 * (BT == 256 ? 1 : 2))
 void proj_dma_kernel(int Bsz, int N, int Npad, int D, int H, int d, const bf16_t* __restrict__ X,
                      const bf16_t* __restrict__ Wq, const bf16_t* __restrict__ Wk, const bf16_t* __restrict__ Wv,
-                     bf16_t* __restrict__ qo, bf16_t* __restrict__ ko, bf16_t* __restrict__ vto, int tiles_x,
+                     h16_t* __restrict__ qo, h16_t* __restrict__ ko, h16_t* __restrict__ vto, int tiles_x,
                      int tiles_w, float qscale, const int* __restrict__ lens, bool skip_q_rows,
                      unsigned long long* __restrict__ counters)
 {
@@ -629,13 +629,13 @@ void proj_dma_kernel(int Bsz, int N, int Npad, int D, int H, int d, const bf16_t
                     const int ct = wr * TA + 32 * a + 8 * r4;  // tile column of register 4*r4 in half 0
                     const int hc = ct >> dsh, c = (ct & (d - 1)) >> 3;
                     u32x2 w;
-                    w[0] = pack_bf16(acc[a][b][4 * r4 + 0] * qs, acc[a][b][4 * r4 + 1] * qs);
-                    w[1] = pack_bf16(acc[a][b][4 * r4 + 2] * qs, acc[a][b][4 * r4 + 3] * qs);
+                    w[0] = pack_f16_sat(acc[a][b][4 * r4 + 0] * qs, acc[a][b][4 * r4 + 1] * qs);
+                    w[1] = pack_f16_sat(acc[a][b][4 * r4 + 2] * qs, acc[a][b][4 * r4 + 3] * qs);
                     *(u32x2*)(lds + (hc * BT + v) * rowb + ((c ^ (v & cmask)) << 4) + 8 * g) = w;
                 }
         }
         __syncthreads();
-        bf16_t* base = (which ? ko : qo) + ((size_t)bb * H + ((w0 - which * HD) >> dsh)) * Npad * d;
+        h16_t* base = (which ? ko : qo) + ((size_t)bb * H + ((w0 - which * HD) >> dsh)) * Npad * d;
 #pragma unroll 4
         for (int e0 = tid; e0 < UNITS; e0 += NT) {
             const int hv = e0 >> (dsh - 3);  // head-in-tile * BT + vector
@@ -661,8 +661,8 @@ void proj_dma_kernel(int Bsz, int N, int Npad, int D, int H, int d, const bf16_t
                     const int slot = (r64 & 48) | vt_slot16(r64 & 15);
                     const int left = N - (i0 + vl);
                     u32x2 w;
-                    w[0] = pack_bf16(left > 0 ? acc[a][b][4 * r4 + 0] : 0.f, left > 1 ? acc[a][b][4 * r4 + 1] : 0.f);
-                    w[1] = pack_bf16(left > 2 ? acc[a][b][4 * r4 + 2] : 0.f, left > 3 ? acc[a][b][4 * r4 + 3] : 0.f);
+                    w[0] = pack_f16_sat(left > 0 ? acc[a][b][4 * r4 + 0] : 0.f, left > 1 ? acc[a][b][4 * r4 + 1] : 0.f);
+                    w[1] = pack_f16_sat(left > 2 ? acc[a][b][4 * r4 + 2] : 0.f, left > 3 ? acc[a][b][4 * r4 + 3] : 0.f);
                     *(u32x2*)(lds + ((hc * (BT / 64) + vb) * d + l) * 128 + (((slot >> 3) ^ (l & 7)) << 4) +
                               2 * (slot & 7)) = w;
                 }
@@ -685,12 +685,12 @@ void proj_dma_kernel(int Bsz, int N, int Npad, int D, int H, int d, const bf16_t
 
 // The stored q carries the score scale and the change to base-2 exponentials:
 // q' = q * scale * log2(e), applied to the fp32 accumulator before the one rounding to
-// bf16, so that the attention kernels get base-2 scores straight out of the MFMA.
+// half precision, so that the attention kernels get base-2 scores straight out of the MFMA.
 inline float q_prescale(const Problem& pb) { return pb.scale * 1.4426950408889634f; }
 
 template <int BT, int WR, int WC>
 hipError_t launch_dma(const Problem& pb, const bf16_t* X, const bf16_t* Wq, const bf16_t* Wk, const bf16_t* Wv,
-                      bf16_t* q, bf16_t* k, bf16_t* vt, hipStream_t s)
+                      h16_t* q, h16_t* k, h16_t* vt, hipStream_t s)
 {
     const float qscale = q_prescale(pb);
     const int tiles_x = pb.B * pb.Npad / BT;
@@ -703,7 +703,7 @@ hipError_t launch_dma(const Problem& pb, const bf16_t* X, const bf16_t* Wq, cons
 }
 
 template <int BT>
-hipError_t launch_bt(const Problem& pb, const bf16_t* X, const bf16_t* Wt, bf16_t* q, bf16_t* k, bf16_t* vt,
+hipError_t launch_bt(const Problem& pb, const bf16_t* X, const bf16_t* Wt, h16_t* q, h16_t* k, h16_t* vt,
                      hipStream_t s)
 {
     const float qscale = q_prescale(pb);
@@ -743,7 +743,7 @@ bool proj_reads_weights_in_place(const Problem& pb, const bf16_t* Wq, const bf16
 }
 
 hipError_t launch_proj_mfma(const Problem& pb, const bf16_t* X, const bf16_t* Wq, const bf16_t* Wk,
-                            const bf16_t* Wv, const bf16_t* Wt, bf16_t* q, bf16_t* k, bf16_t* vt, hipStream_t s)
+                            const bf16_t* Wv, const bf16_t* Wt, h16_t* q, h16_t* k, h16_t* vt, hipStream_t s)
 {
     // Largest square tile that divides the per-matrix column count (so a tile never
     // mixes q, k and v columns) and still gives every CU a few tiles.

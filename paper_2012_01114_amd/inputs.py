@@ -113,3 +113,50 @@ def make_inputs(w: Workload, zero_wq: bool = False) -> Tuple[dict, dict]:
     stored["lens"] = lens
     f64["lens"] = lens
     return stored, f64
+
+
+# Key-level profiles for make_level_inputs: nats added to every score of key j (n keys).
+def _levels_ramp(n: int) -> np.ndarray:
+    """Falls linearly from 60 at key 0 to 0 at key n-1: along a walk towards key 0 the largest
+    score of a row keeps growing, by far more than any fixed slack."""
+    return 60.0 * (1.0 - np.arange(n) / max(n - 1, 1))
+
+
+def _levels_steps(n: int) -> np.ndarray:
+    """Three plateaus, 18 / 9 / 0 nats for keys [0, 8) / [8, 40) / [40, n): each step up outweighs
+    everything met before it by a few hundred times per key, while the many keys of the lower
+    plateau keep a share of the row sum that a wrong rescaling would multiply."""
+    lv = np.zeros(n)
+    lv[:40] = 9.0
+    lv[:8] = 18.0
+    return lv
+
+
+LEVEL_PROFILES = {"ramp": _levels_ramp, "steps": _levels_steps}
+
+
+def make_level_inputs(w: Workload, profile: str, scale: float) -> Tuple[dict, dict]:
+    """The draw of make_inputs with a designed level added to the scores of every key.
+
+    Input channel 0 carries a constant c for every vector and feeds only one unit direction u of
+    each head's q; channel 1 carries t_j and feeds only the same direction of k; neither reaches v.
+    Every score of key j thus gains scale * c * t_j = LEVEL_PROFILES[profile](n)[j] nats on top of
+    the random part, for every row alike, so the row maxima move along the key axis as designed.
+    `scale` is the score scale the run will use (1/sqrt(d_k) by default)."""
+    stored, f64 = make_inputs(w)
+    rng = np.random.default_rng(w.seed + 77)
+    levels = LEVEL_PROFILES[profile](w.n)
+    c = 8.0
+    x = f64["X"].copy()
+    x[:, :, 0] = c
+    x[:, :, 1] = levels[None, :] / (scale * c)
+    ws = {k: f64[k].copy() for k in ("Wq", "Wk", "Wv")}
+    for k in ws:
+        ws[k][0:2, :] = 0.0
+    for h in range(w.n_heads):
+        u = rng.choice([-1.0, 1.0], size=w.d_k) / np.sqrt(w.d_k)   # |u| = 1
+        ws["Wq"][0, h * w.d_k:(h + 1) * w.d_k] = u
+        ws["Wk"][1, h * w.d_k:(h + 1) * w.d_k] = u
+    for key, arr in (("X", x), ("Wq", ws["Wq"]), ("Wk", ws["Wk"]), ("Wv", ws["Wv"])):
+        stored[key], f64[key] = round_to_storage(arr, w.dtype)
+    return stored, f64

@@ -1,6 +1,7 @@
 """Shared plumbing of the GPU parity tests: run the library through its C ABI
 binding on seeded inputs and fetch what the CPU checker says for the same inputs."""
 import math
+import os
 
 import numpy as np
 
@@ -24,6 +25,40 @@ def tol_check(got, ref, dtype):
     assert not bad.any(), (f"{int(bad.sum())} of {bad.size} elements out of tolerance; "
                            f"max err {err.max():.3e} at {np.unravel_index(err.argmax(), err.shape)}")
     return float(err.max())
+
+
+def report_max_err(case, err, dtype):
+    """One line per parity case (shown by `pytest -rA`), also appended to the file that
+    ATTN_PARITY_LOG names, if set."""
+    line = f"[maxerr] {case}: {err:.3e} ({dtype}; bar {'2e-2 abs' if dtype == 'bf16' else '1e-5 rel'})"
+    print(line, flush=True)
+    path = os.environ.get("ATTN_PARITY_LOG")
+    if path:
+        with open(path, "a") as fh:
+            fh.write(line + "\n")
+
+
+def expected_phys_blocks(w, scheme, lens=None, skip_padded_rows=False, block=32):
+    """Score blocks of `block` x `block` pairs that hold at least one allowed pair, summed over
+    batch items and heads, enumerated from the pair predicate itself: pair (i, j) is allowed iff
+    j < len, (masked scheme) j <= i, and (padded rows left out) i < len.  Row blocks are the
+    32-row groups a wavefront owns, key blocks the 32-key groups it walks."""
+    n = w.n
+    nb = (n + block - 1) // block
+    total = 0
+    i = np.arange(n)[:, None]
+    j = np.arange(n)[None, :]
+    for b in range(w.batch):
+        L = n if lens is None else int(min(max(int(lens[b]), 0), n))
+        ok = np.broadcast_to(j < L, (n, n)).copy()
+        if scheme == inputs.SCHEME_CAUSAL:
+            ok &= j <= i
+        if skip_padded_rows:
+            ok &= i < L
+        pad = np.zeros((nb * block, nb * block), dtype=bool)
+        pad[:n, :n] = ok
+        total += int(pad.reshape(nb, block, nb, block).any(axis=(1, 3)).sum())
+    return total * w.n_heads
 
 
 def default_scale(w, scale):
