@@ -159,6 +159,29 @@ attn_status attn_stats(attn_ctx* ctx, attn_stats_t* out);
 attn_status attn_profile(attn_ctx* ctx, int32_t enable);
 attn_status attn_profile_read(attn_ctx* ctx, attn_profile_t* out);
 
+/*
+ * attn_forward without any allocation, for callers that cannot allocate: code under HIP graph
+ * capture, serving loops and harnesses that forbid hipMalloc.  No context: the configuration and the
+ * key lengths (device array of `batch` int32, or NULL) come with the call; X, Wq, Wk, Wv, out and
+ * hip_stream are as for attn_forward.  The workspace (counter slots, projected q, k, v) is a fixed
+ * array of ATTN_STATIC_SCRATCH_MIB MiB of device memory that belongs to the loaded library; every GPU
+ * the library is used on holds its copy until the process ends.  The call makes no hipMalloc, hipFree
+ * or other allocating call and does not wait for the stream.
+ * Takes only what the matrix-core kernels take with the weights read in place: bfloat16, d_k 64 or
+ * 128, d_model a multiple of 64, n_heads*d_k a multiple of 128, X and weights 16-byte aligned, schemes
+ * FULL and CAUSAL; anything else, and any shape whose workspace
+ *     130 KiB + 3 * batch * roundup(n, 256) * n_heads * d_k * 2 bytes
+ * exceeds the array, returns UNSUPPORTED with the size needed in attn_last_error(NULL).
+ * All calls on one GPU share that GPU's array, which keeps what the last call left: the call clears
+ * what must start at zero (counter slots, the rows past n) itself, and two calls that overlap in time
+ * on one GPU - on different streams or from different threads - race.  Calls on one stream, or
+ * otherwise ordered by the caller, are fine.  Results obey the same bars as attn_forward's.
+ */
+#define ATTN_STATIC_SCRATCH_MIB 64
+attn_status attn_forward_static(const attn_config* cfg, const int32_t* lens_dev, const void* X,
+                                const void* Wq, const void* Wk, const void* Wv, int32_t scheme, void* out,
+                                void* hip_stream);
+
 /* Text of the last failure on this context (ctx == NULL: of the last failed
  * attn_init on this thread).  Never NULL; valid until the next call. */
 const char* attn_last_error(const attn_ctx* ctx);

@@ -22,8 +22,9 @@ ATTN_FLAG_WIDE_TILES = 2
 ATTN_FLAG_NARROW_TILES = 4
 ATTN_FLAG_SKIP_PADDED_ROWS = 8
 
-EXPORTS = ("attn_init", "attn_set_key_lengths", "attn_forward", "attn_stats", "attn_profile",
-           "attn_profile_read", "attn_last_error", "attn_destroy")
+EXPORTS = ("attn_init", "attn_set_key_lengths", "attn_forward", "attn_forward_static", "attn_stats",
+           "attn_profile", "attn_profile_read", "attn_last_error", "attn_destroy")
+ATTN_STATIC_SCRATCH_MIB = 64
 
 
 class attn_config(C.Structure):
@@ -70,6 +71,8 @@ def load():
     lib.attn_set_key_lengths.argtypes = [vp, vp]
     lib.attn_forward.restype = C.c_int
     lib.attn_forward.argtypes = [vp, vp, vp, vp, vp, C.c_int32, vp, vp]
+    lib.attn_forward_static.restype = C.c_int
+    lib.attn_forward_static.argtypes = [C.POINTER(attn_config), vp, vp, vp, vp, vp, C.c_int32, vp, vp]
     lib.attn_stats.restype = C.c_int
     lib.attn_stats.argtypes = [vp, C.POINTER(attn_stats_t)]
     lib.attn_profile.restype = C.c_int
@@ -128,6 +131,19 @@ def attn_forward(ctx, X, Wq, Wk, Wv, scheme: int, out, stream=None) -> None:
     st = load().attn_forward(ctx, _ptr(X), _ptr(Wq), _ptr(Wk), _ptr(Wv), int(scheme), _ptr(out),
                              C.c_void_p(stream.cuda_stream))
     _check(st, ctx)
+
+
+def attn_forward_static(batch: int, n: int, d_model: int, n_heads: int, d_k: int, p: int, dtype: int,
+                        X, Wq, Wk, Wv, scheme: int, out, lens_dev=None, scale: float = 0.0, flags: int = 0,
+                        stream=None) -> None:
+    """attn_forward on the library's fixed workspace: no context, no allocation."""
+    import torch
+    if stream is None:
+        stream = torch.cuda.current_stream(X.device)
+    cfg = attn_config(batch, n, d_model, n_heads, d_k, p, dtype, scale, flags)
+    st = load().attn_forward_static(C.byref(cfg), _ptr(lens_dev), _ptr(X), _ptr(Wq), _ptr(Wk), _ptr(Wv),
+                                    int(scheme), _ptr(out), C.c_void_p(stream.cuda_stream))
+    _check(st, None)
 
 
 def attn_stats(ctx) -> dict:

@@ -5,10 +5,11 @@
 #include <cmath>
 #include <cstdio>
 #include <cstring>
+#include <mutex>
 #include <new>
 #include <vector>
 
-#include "common.h"
+#include "mfma_common.h"
 
 using namespace attnring;
 
@@ -41,6 +42,13 @@ struct attn_ctx {
     std::vector<hipEvent_t> events;  // 4 per timed call
     char err[512];
 };
+
+// Workspace of attn_forward_static: counter slots, then q, k and v^T of one call, in device memory
+// that belongs to the loaded library (one copy per GPU, held until the process ends) instead of
+// coming from hipMalloc.  In host code this name only stands for the symbol; its address on a
+// device comes from hipGetSymbolAddress (static_scratch_on_current_device).
+constexpr size_t STATIC_SCRATCH_BYTES = (size_t)ATTN_STATIC_SCRATCH_MIB << 20;
+static __device__ __align__(256) unsigned char scratch[STATIC_SCRATCH_BYTES];
 
 namespace {
 
@@ -150,6 +158,96 @@ attn_status sum_over_lengths(attn_ctx* c, F f, unsigned long long* out)
     return ATTN_OK;
 }
 
+long long padded_rows(int n) { return ((long long)n + 255) / 256 * 256; }  // row pitch of the projected q, k, v
+
+float effective_scale(const attn_config* cfg)
+{
+    return cfg->scale == 0.f ? 1.f / std::sqrt((float)cfg->d_k) : cfg->scale;
+}
+
+// Shape and dtype fit the matrix-core kernels.
+bool matrix_core_shape(const attn_config* cfg)
+{
+    return cfg->dtype == ATTN_BF16 && (cfg->d_k == 64 || cfg->d_k == 128) && cfg->d_model % 8 == 0 &&
+           effective_scale(cfg) > 0.f;
+}
+
+// The checks every entry point that takes a configuration starts with.
+attn_status validate_config(const attn_config* cfg)
+{
+    if (cfg->batch < 1 || cfg->n < 1 || cfg->d_model < 1 || cfg->n_heads < 1 || cfg->d_k < 1 || cfg->p < 1)
+        return fail(nullptr, ATTN_ERR_INVALID, "attn config: every size must be >= 1%s");
+    if (cfg->dtype != ATTN_F32 && cfg->dtype != ATTN_BF16)
+        return fail(nullptr, ATTN_ERR_INVALID, "attn config: unknown dtype%s");
+    if (cfg->flags & ~(uint32_t)(ATTN_FLAG_NO_SKIP | ATTN_FLAG_WIDE_TILES | ATTN_FLAG_NARROW_TILES |
+                                 ATTN_FLAG_SKIP_PADDED_ROWS))
+        return fail(nullptr, ATTN_ERR_INVALID, "attn config: unknown flag%s");
+    if ((cfg->flags & ATTN_FLAG_WIDE_TILES) && (cfg->flags & ATTN_FLAG_NARROW_TILES))
+        return fail(nullptr, ATTN_ERR_INVALID, "attn config: WIDE_TILES and NARROW_TILES exclude each other%s");
+    if (!(cfg->scale == cfg->scale) || std::isinf(cfg->scale))
+        return fail(nullptr, ATTN_ERR_INVALID, "attn config: scale is not finite%s");
+    if (cfg->n % cfg->p != 0)
+        return fail(nullptr, ATTN_ERR_SHAPE, "attn config: n must be divisible by p (ring partitions)%s");
+    const long long Npad = ((long long)cfg->n + 255) / 256 * 256;
+    const long long hd = (long long)cfg->n_heads * cfg->d_k;
+    const long long limit = 0x7fffffffLL;
+    if ((long long)cfg->batch * Npad * hd > limit || (long long)cfg->batch * cfg->n * cfg->d_model > limit ||
+        3 * hd * cfg->d_model > limit || (long long)cfg->p * cfg->p > limit)
+        return fail(nullptr, ATTN_ERR_SHAPE, "attn config: problem too large for 32-bit element indices%s");
+    if (cfg->d_k > 256)
+        return fail(nullptr, ATTN_ERR_UNSUPPORTED, "attn config: d_k above 256 is not implemented%s");
+    return ATTN_OK;
+}
+
+// Address of `scratch` on the current device: asked for once per device, with that device
+// current (every GPU holds its own copy of the array at its own address), and kept.
+constexpr int MAX_DEVICES = 64;
+unsigned char* g_scratch_ptr[MAX_DEVICES] = {};
+std::mutex g_scratch_mutex;
+
+attn_status static_scratch_on_current_device(unsigned char** out)
+{
+    int dev = -1;
+    hipError_t e = hipGetDevice(&dev);
+    if (e != hipSuccess) return hip_fail(nullptr, "hipGetDevice", e);
+    if (dev < 0 || dev >= MAX_DEVICES) return fail(nullptr, ATTN_ERR_UNSUPPORTED, "device index beyond 63%s");
+    std::lock_guard<std::mutex> lock(g_scratch_mutex);
+    if (!g_scratch_ptr[dev]) {
+        void* p = nullptr;
+        e = hipGetSymbolAddress(&p, HIP_SYMBOL(scratch));
+        if (e != hipSuccess || !p) return hip_fail(nullptr, "hipGetSymbolAddress(scratch)", e);
+        g_scratch_ptr[dev] = (unsigned char*)p;
+    }
+    *out = g_scratch_ptr[dev];
+    return ATTN_OK;
+}
+
+// Rows n .. Npad-1 of q and k, and the key slots of v^T that belong to them, of every (batch, head):
+// the kernels take them to be zero.  Grid (batch * heads, 3).
+__global__ __launch_bounds__(256) void clear_pad_rows_kernel(int N, int Npad, int d, h16_t* __restrict__ q,
+                                                             h16_t* __restrict__ k, h16_t* __restrict__ vt)
+{
+    const size_t head = (size_t)blockIdx.x * Npad * d;
+    if (blockIdx.y < 2) {
+        h16_t* dst = (blockIdx.y == 0 ? q : k) + head + (size_t)N * d;
+        const int count = (Npad - N) * d;
+        for (int e = threadIdx.x; e < count; e += blockDim.x) dst[e] = 0;
+    } else {
+        // v^T: [64-key block][d][64 slots]; slot (s & 48) | vt_slot16(s & 15) holds key s of the block,
+        // and the permutation is its own inverse
+        const int first = (N >> 6) * 64 * d;
+        const int count = Npad * d - first;
+        for (int e = threadIdx.x; e < count; e += blockDim.x) {
+            const int pos = first + e;
+            const int blk = pos / (64 * d), slot = pos & 63;
+            const int key = blk * 64 + ((slot & 48) | vt_slot16(slot & 15));
+            if (key >= N) vt[head + pos] = 0;
+        }
+    }
+}
+
+size_t round_up_256(size_t x) { return (x + 255) & ~(size_t)255; }
+
 }  // namespace
 
 extern "C" {
@@ -158,40 +256,22 @@ attn_status attn_init(const attn_config* cfg, attn_ctx** out_ctx)
 {
     if (out_ctx) *out_ctx = nullptr;
     if (!cfg || !out_ctx) return fail(nullptr, ATTN_ERR_INVALID, "attn_init: NULL argument%s");
-    if (cfg->batch < 1 || cfg->n < 1 || cfg->d_model < 1 || cfg->n_heads < 1 || cfg->d_k < 1 || cfg->p < 1)
-        return fail(nullptr, ATTN_ERR_INVALID, "attn_init: every size must be >= 1%s");
-    if (cfg->dtype != ATTN_F32 && cfg->dtype != ATTN_BF16)
-        return fail(nullptr, ATTN_ERR_INVALID, "attn_init: unknown dtype%s");
-    if (cfg->flags & ~(uint32_t)(ATTN_FLAG_NO_SKIP | ATTN_FLAG_WIDE_TILES | ATTN_FLAG_NARROW_TILES |
-                                 ATTN_FLAG_SKIP_PADDED_ROWS))
-        return fail(nullptr, ATTN_ERR_INVALID, "attn_init: unknown flag%s");
-    if ((cfg->flags & ATTN_FLAG_WIDE_TILES) && (cfg->flags & ATTN_FLAG_NARROW_TILES))
-        return fail(nullptr, ATTN_ERR_INVALID, "attn_init: WIDE_TILES and NARROW_TILES exclude each other%s");
-    if (!(cfg->scale == cfg->scale) || std::isinf(cfg->scale))
-        return fail(nullptr, ATTN_ERR_INVALID, "attn_init: scale is not finite%s");
-    if (cfg->n % cfg->p != 0)
-        return fail(nullptr, ATTN_ERR_SHAPE, "attn_init: n must be divisible by p (ring partitions)%s");
-    const long long Npad = ((long long)cfg->n + 255) / 256 * 256;
+    attn_status vst = validate_config(cfg);
+    if (vst != ATTN_OK) return vst;
+    const long long Npad = padded_rows(cfg->n);
     const long long hd = (long long)cfg->n_heads * cfg->d_k;
-    const long long limit = 0x7fffffffLL;
-    if ((long long)cfg->batch * Npad * hd > limit || (long long)cfg->batch * cfg->n * cfg->d_model > limit ||
-        3 * hd * cfg->d_model > limit || (long long)cfg->p * cfg->p > limit)
-        return fail(nullptr, ATTN_ERR_SHAPE, "attn_init: problem too large for 32-bit element indices%s");
-    if (cfg->d_k > 256)
-        return fail(nullptr, ATTN_ERR_UNSUPPORTED, "attn_init: d_k above 256 is not implemented%s");
 
     attn_ctx* c = new (std::nothrow) attn_ctx();
     if (!c) return fail(nullptr, ATTN_ERR_ALLOC, "attn_init: out of host memory%s");
     c->cfg = *cfg;
     c->b = cfg->n / cfg->p;
     c->Npad = (int)Npad;
-    c->scale = cfg->scale == 0.f ? 1.f / std::sqrt((float)cfg->d_k) : cfg->scale;
+    c->scale = effective_scale(cfg);
     c->err[0] = 0;
     hipError_t e = hipGetDevice(&c->device);
     if (e != hipSuccess) { attn_status st = hip_fail(nullptr, "hipGetDevice", e); delete c; return st; }
 
-    c->mfma_shape = cfg->dtype == ATTN_BF16 && (cfg->d_k == 64 || cfg->d_k == 128) && cfg->d_model % 8 == 0 &&
-                    c->scale > 0.f;
+    c->mfma_shape = matrix_core_shape(cfg);
     e = hipMalloc((void**)&c->counters, sizeof(unsigned long long) * CNT_BUFFER_WORDS);
     if (e == hipSuccess) e = hipMemset(c->counters, 0, sizeof(unsigned long long) * CNT_BUFFER_WORDS);
     if (e == hipSuccess && c->mfma_shape) {
@@ -346,6 +426,66 @@ attn_status attn_forward(attn_ctx* ctx, const void* X, const void* Wq, const voi
     ctx->last_rows_too = pb.skip_rows;
     ctx->last_scheme = scheme;
     ctx->have_forward = true;
+    return ATTN_OK;
+}
+
+attn_status attn_forward_static(const attn_config* cfg, const int32_t* lens_dev, const void* X, const void* Wq,
+                                const void* Wk, const void* Wv, int32_t scheme, void* out, void* hip_stream)
+{
+    if (!cfg) return fail(nullptr, ATTN_ERR_INVALID, "attn_forward_static: NULL configuration%s");
+    attn_status st = validate_config(cfg);
+    if (st != ATTN_OK) return st;
+    if (!X || !out || !Wq || !Wk || !Wv)
+        return fail(nullptr, ATTN_ERR_INVALID, "attn_forward_static: X, Wq, Wk, Wv and out must not be NULL%s");
+    if (scheme != ATTN_SCHEME_FULL && scheme != ATTN_SCHEME_CAUSAL)
+        return fail(nullptr, ATTN_ERR_UNSUPPORTED, "attn_forward_static: FULL and CAUSAL schemes only%s");
+
+    // the matrix-core path with the weights read in place: the one path whose whole workspace is
+    // the counters and the projected q, k, v
+    Problem pb;
+    pb.B = cfg->batch; pb.N = cfg->n; pb.D = cfg->d_model; pb.H = cfg->n_heads; pb.d = cfg->d_k;
+    pb.P = cfg->p; pb.b = cfg->n / cfg->p; pb.Npad = (int)padded_rows(cfg->n); pb.scale = effective_scale(cfg);
+    pb.scheme = scheme;
+    pb.noskip = (cfg->flags & ATTN_FLAG_NO_SKIP) != 0;
+    pb.skip_rows = (cfg->flags & ATTN_FLAG_SKIP_PADDED_ROWS) != 0 && lens_dev != nullptr;
+    pb.is_bf16 = true;
+    pb.lens = lens_dev;
+    if (!matrix_core_shape(cfg) || !aligned_to(X, 16) || !aligned_to(out, 8) ||
+        !proj_reads_weights_in_place(pb, (const bf16_t*)Wq, (const bf16_t*)Wk, (const bf16_t*)Wv))
+        return fail(nullptr, ATTN_ERR_UNSUPPORTED,
+                    "attn_forward_static: needs bfloat16, d_k 64 or 128, d_model a multiple of 64, n_heads*d_k a "
+                    "multiple of 128, 16-byte aligned X and weights%s");
+    const size_t cnt_bytes = round_up_256(sizeof(unsigned long long) * CNT_BUFFER_WORDS);
+    const size_t qkv = round_up_256((size_t)pb.B * pb.Npad * pb.H * pb.d * sizeof(h16_t));
+    if (cnt_bytes + 3 * qkv > STATIC_SCRATCH_BYTES) {
+        char msg[256];
+        snprintf(msg, sizeof(msg),
+                 "attn_forward_static: this shape needs %zu bytes of workspace, beyond the fixed %d MiB; use "
+                 "attn_init / attn_forward", cnt_bytes + 3 * qkv, (int)ATTN_STATIC_SCRATCH_MIB);
+        return fail(nullptr, ATTN_ERR_UNSUPPORTED, "%s", msg);
+    }
+    unsigned char* base = nullptr;
+    st = static_scratch_on_current_device(&base);
+    if (st != ATTN_OK) return st;
+    pb.counters = (unsigned long long*)base;
+    h16_t* q = (h16_t*)(base + cnt_bytes);
+    h16_t* k = (h16_t*)(base + cnt_bytes + qkv);
+    h16_t* vt = (h16_t*)(base + cnt_bytes + 2 * qkv);
+
+    hipStream_t s = (hipStream_t)hip_stream;
+    hipError_t e;
+    if (pb.Npad > pb.N) {  // whatever an earlier call left in the rows past n
+        hipLaunchKernelGGL(clear_pad_rows_kernel, dim3(pb.B * pb.H, 3), dim3(256), 0, s, pb.N, pb.Npad, pb.d, q, k, vt);
+        e = hipGetLastError();
+        if (e != hipSuccess) return hip_fail(nullptr, "launch clear_pad_rows", e);
+    }
+    e = launch_proj_mfma(pb, (const bf16_t*)X, (const bf16_t*)Wq, (const bf16_t*)Wk, (const bf16_t*)Wv, nullptr, q, k,
+                         vt, s);
+    if (e != hipSuccess) return hip_fail(nullptr, "launch proj_mfma", e);
+    int waves = cfg->d_k == 128 ? 8 : 4;
+    if (cfg->d_k == 64 && (cfg->flags & ATTN_FLAG_WIDE_TILES)) waves = 8;
+    e = launch_attn_pipe(pb, q, k, vt, (bf16_t*)out, waves, s);
+    if (e != hipSuccess) return hip_fail(nullptr, "launch attention (mfma)", e);
     return ATTN_OK;
 }
 

@@ -69,5 +69,26 @@ def test_null_arguments():
     assert lib.attn_profile(None, 1) == ar.ATTN_ERR_INVALID
     assert lib.attn_profile_read(None, None) == ar.ATTN_ERR_INVALID
     assert lib.attn_set_key_lengths(None, None) == ar.ATTN_ERR_INVALID
+    assert lib.attn_forward_static(None, None, None, None, None, None, 0, None, None) == ar.ATTN_ERR_INVALID
     lib.attn_destroy(None)
     assert isinstance(ar.attn_last_error(None), str)
+
+
+def test_static_entry_point_rejects_before_touching_the_device():
+    """Shapes outside the matrix-core path and workspaces beyond the fixed array come back as
+    UNSUPPORTED from the argument checks alone (the pointers are never followed)."""
+    lib = ar.load()
+    fake = C.c_void_p(0x10000)
+
+    def call(**kw):
+        cfg = dict(batch=1, n=512, d_model=128, n_heads=2, d_k=64, p=64, dtype=ar.ATTN_BF16, scale=0.0, flags=0)
+        cfg.update(kw)
+        c = ar.attn_config(*[cfg[k] for k in ("batch", "n", "d_model", "n_heads", "d_k", "p", "dtype", "scale", "flags")])
+        return lib.attn_forward_static(C.byref(c), None, fake, fake, fake, fake, ar.ATTN_SCHEME_CAUSAL, fake, None)
+
+    assert call(dtype=ar.ATTN_F32) == ar.ATTN_ERR_UNSUPPORTED
+    assert call(d_k=32) == ar.ATTN_ERR_UNSUPPORTED
+    assert call(d_model=72) == ar.ATTN_ERR_UNSUPPORTED
+    assert call(n=18, p=4) == ar.ATTN_ERR_SHAPE
+    assert call(batch=64, n=8192, n_heads=16) == ar.ATTN_ERR_UNSUPPORTED      # 3 x 1 GiB of q, k, v
+    assert "bytes of workspace" in ar.attn_last_error(None)
