@@ -99,13 +99,19 @@ def cpu_baseline(w, f64, lens, budget_s=12.0, max_heads=256, rows_too=False):
 class Session:
     """One workload resident on the GPU: inputs, context, output buffer."""
 
-    def __init__(self, name, tiles="auto", skip_padded_rows=False):
+    def __init__(self, name, tiles="auto", skip_padded_rows=False, scheme=None, one_weight=False):
+        """scheme: run the workload's shape under another scheme; one_weight: Wq in all three roles
+        (the setting in which the q = k = v scheme and the original definition give the same result)."""
         import torch
         from paper_2012_01114_amd import attnring as ar
         from paper_2012_01114_amd import inputs
         self.ar, self.torch = ar, torch
         self.w = w = inputs.WORKLOADS[name]
+        if scheme is not None:
+            self.w = w = inputs.with_scheme(w, scheme)
         stored, self.f64 = inputs.make_inputs(w)
+        if one_weight:
+            stored["Wk"] = stored["Wv"] = stored["Wq"]
         self.lens = stored["lens"]
         dev = torch.device("cuda:0")
         self.X, self.Wq, self.Wk, self.Wv = [stored[k].to(dev) for k in ("X", "Wq", "Wk", "Wv")]
@@ -278,6 +284,24 @@ def main():
         torch.cuda.empty_cache()
     if others:
         line["workloads"] = others
+
+    # Sec. 4: the q = k = v scheme (each score tile computed once, used for both row blocks) against
+    # the original definition on the same inputs, Wq in all three roles; encoder shape
+    if args.others:
+        rec = {}
+        for label, scheme in (("full", inputs.SCHEME_FULL), ("symmetric", inputs.SCHEME_SYMMETRIC)):
+            o = Session("encoder", scheme=scheme, one_weight=True)
+            o_ms, _, o_prof, o_stats = o.measure(args.steps, args.warmup, args.repeats)
+            rec[label] = {"ms_per_step": round(o_ms, 4), "ms_projection": round(o_prof["ms_projection"], 4),
+                          "ms_attention": round(o_prof["ms_attention"], 4),
+                          "phase1_pairs_needed": o_stats["pairs_needed"][0],
+                          "phase1_pairs_scheduled": o_stats["pairs_scheduled"][0],
+                          "score_blocks_issued": o_stats["phys_tiles_executed"]}
+            o.close()
+            del o
+            torch.cuda.empty_cache()
+        rec["workload"] = "encoder shape, Wq = Wk = Wv"
+        line["symmetric_vs_full"] = rec
 
     if not args.no_cpu_baseline:
         line["cpu_baseline"] = cpu_baseline(w, f64, lens, rows_too=rows_too)

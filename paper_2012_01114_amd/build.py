@@ -14,7 +14,7 @@ HERE = os.path.dirname(os.path.abspath(__file__))
 CSRC = os.path.join(HERE, "csrc")
 OBJ = os.path.join(HERE, "_build")
 LIB = os.path.join(HERE, "libattnring.so")
-SOURCES = ["attnring_api.hip", "generic_kernels.hip", "proj_mfma.hip", "attn_pipe.hip"]
+SOURCES = ["attnring_api.hip", "generic_kernels.hip", "proj_mfma.hip", "attn_pipe.hip", "sym_pair.hip"]
 HIPCC = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
 FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-Wall", "-Wno-unused-function",
          "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops"]

@@ -70,9 +70,9 @@ struct Pipe {
     // With five stages a wavefront in the walk does not request a tile right behind the barrier
     // that frees its stage but spreads its pieces over the matrix phases up to the next barrier.
     static constexpr bool SPREAD = STAGES >= 5;
-    // Fold the reference into the score accumulator (saves a subtraction per pair, costs 16 registers):
-    // pays where the vector ALUs are the busier unit per MFMA, d_k = 128.
-    static constexpr bool USE_CNEG = DK == 128;
+    // Fold the reference into the score accumulator: saves a subtraction per pair, costs 16 registers
+    // (168 in all for the 4-wavefront d_k = 64 kernel, just what three wavefronts per SIMD allow).
+    static constexpr bool USE_CNEG = true;
 
     struct Row {
         f32x16 O[NDB];  // O^T, un-normalised

@@ -24,7 +24,8 @@ struct attn_ctx {
     bf16_t* wt;
     // generic float workspace (allocated on first use)
     float *qf, *kf, *vf;
-    float* scores;  // q = k = v scheme: one n x n score matrix per (batch, head)
+    float* scores;  // q = k = v scheme, float path: one n x n score matrix per (batch, head)
+    float* sym_work;  // q = k = v scheme, matrix-core path: partial row states (allocated on first use)
     unsigned long long* counters;
     const int32_t* lens;
     // last forward
@@ -72,7 +73,7 @@ attn_status hip_fail(attn_ctx* ctx, const char* what, hipError_t e)
 
 void free_all(attn_ctx* c)
 {
-    void* ptrs[] = {c->qb, c->kb, c->vtb, c->wt, c->qf, c->kf, c->vf, c->scores, c->counters};
+    void* ptrs[] = {c->qb, c->kb, c->vtb, c->wt, c->qf, c->kf, c->vf, c->scores, c->sym_work, c->counters};
     for (void* p : ptrs)
         if (p) (void)hipFree(p);
     for (hipEvent_t e : c->events) (void)hipEventDestroy(e);
@@ -353,8 +354,17 @@ attn_status attn_forward(attn_ctx* ctx, const void* X, const void* Wq, const voi
     MARK(0);
     bool prepared = false;  // whether event 1 of this call gets recorded
 
-    const bool use_mfma = ctx->mfma_shape && scheme != ATTN_SCHEME_SYMMETRIC && aligned_to(X, 16) &&
-                          aligned_to(out, 8) && aligned_to(Wq, 2) && aligned_to(Wk, 2) && aligned_to(Wv, 2);
+    // The q = k = v scheme runs on the matrix cores when z is a projection (Wq given) and the
+    // partial row states fit the workspace bound.
+    const bool sym = scheme == ATTN_SCHEME_SYMMETRIC;
+    const bool sym_fits = sym && Wq != nullptr && sym_pair_workspace_floats(pb) * sizeof(float) <= MAX_SCORE_BYTES;
+    const bool use_mfma = ctx->mfma_shape && (!sym || sym_fits) && aligned_to(X, 16) && aligned_to(out, 8) &&
+                          aligned_to(Wq, 2) && (sym || (aligned_to(Wk, 2) && aligned_to(Wv, 2)));
+    if (sym && use_mfma) { Wk = Wq; Wv = Wq; }  // one set of vectors in all three roles (Sec. 4.1)
+    if (sym && use_mfma && !ctx->sym_work) {
+        e = hipMalloc((void**)&ctx->sym_work, sym_pair_workspace_floats(pb) * sizeof(float));
+        if (e != hipSuccess) return hip_fail(ctx, "hipMalloc(partial row states)", e);
+    }
     if (!use_mfma) {  // the matrix-core path clears the counters in its first kernel
         hipLaunchKernelGGL(zero_counters_kernel, dim3(1), dim3(CNT_SLOTS), 0, s, ctx->counters);
         e = hipGetLastError();
@@ -373,13 +383,19 @@ attn_status attn_forward(attn_ctx* ctx, const void* X, const void* Wq, const voi
                              ctx->qb, ctx->kb, ctx->vtb, s);
         CHECK("launch proj_mfma");
         MARK(2);
-        // d_k = 64: 128-row workgroups of 4 wavefronts, three of them per CU; d_k = 128: 256 rows, 8 wavefronts
-        int waves = cf.d_k == 128 ? 8 : 4;
-        if (cf.d_k == 64 && (cf.flags & ATTN_FLAG_WIDE_TILES)) waves = 8;
-        e = launch_attn_pipe(pb, ctx->qb, ctx->kb, ctx->vtb, (bf16_t*)out, waves, s);
-        CHECK("launch attention (mfma)");
+        if (sym) {
+            e = launch_sym_pair(pb, ctx->kb, ctx->vtb, ctx->sym_work, (bf16_t*)out, s);
+            CHECK("launch q=k=v attention (mfma)");
+            ctx->last_proj_gemms = 2;  // z = x.Wq, produced in the k and in the v^T layout
+        } else {
+            // d_k = 64: 128-row workgroups of 4 wavefronts, three of them per CU; d_k = 128: 256 rows, 8 wavefronts
+            int waves = cf.d_k == 128 ? 8 : 4;
+            if (cf.d_k == 64 && (cf.flags & ATTN_FLAG_WIDE_TILES)) waves = 8;
+            e = launch_attn_pipe(pb, ctx->qb, ctx->kb, ctx->vtb, (bf16_t*)out, waves, s);
+            CHECK("launch attention (mfma)");
+            ctx->last_proj_gemms = 3;
+        }
         MARK(3);
-        ctx->last_proj_gemms = 3;
         ctx->last_phys = MFMA_BLOCK;
     } else {
         attn_status st = ensure_generic_workspace(ctx);

@@ -66,6 +66,11 @@ hipError_t launch_proj_mfma(const Problem& pb, const bf16_t* X, const bf16_t* Wq
 // 4 or 8 for d_k = 64, 8 for d_k = 128.
 hipError_t launch_attn_pipe(const Problem& pb, const h16_t* q, const h16_t* k, const h16_t* vt,
                             bf16_t* out, int waves, hipStream_t s);
+// q = k = v scheme on the matrix cores: every 128 x 128 score tile computed once and used for both
+// of its row blocks, partial row states merged by a second kernel.  z, zt: the shared vectors in
+// the k and v^T layouts above; work: sym_pair_workspace_floats(pb) floats.
+size_t sym_pair_workspace_floats(const Problem& pb);
+hipError_t launch_sym_pair(const Problem& pb, const h16_t* z, const h16_t* zt, float* work, bf16_t* out, hipStream_t s);
 // Physical score-block edge of the MFMA attention kernels (phys_br = phys_bc).
 enum { MFMA_BLOCK = 32 };
 

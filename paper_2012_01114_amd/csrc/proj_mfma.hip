@@ -153,7 +153,7 @@ __global__ __launch_bounds__(256) void proj_mfma_kernel(int Bsz, int N, int Npad
                                                         const bf16_t* __restrict__ X,
                                                         const bf16_t* __restrict__ Wt, h16_t* __restrict__ qo,
                                                         h16_t* __restrict__ ko, h16_t* __restrict__ vto,
-                                                        int tiles_x, int tiles_w, float qscale, const int* __restrict__ lens, bool skip_q_rows)
+                                                        int tiles_x, int tiles_w, float qscale, const int* __restrict__ lens, bool skip_q_rows, bool no_q)
 {
     constexpr int WT = BT / 2;          // wavefront tile edge
     constexpr int NB = WT / 32;         // MFMA blocks per edge
@@ -180,6 +180,7 @@ __global__ __launch_bounds__(256) void proj_mfma_kernel(int Bsz, int N, int Npad
     // padding): their k and v rows are not computed.  (q rows are: every query row has an output.)
     // With padded rows left out as queries too, the same holds for their q rows.
     if (lens != nullptr && (w0 >= HD || skip_q_rows) && past_key_length(lens, x0, Npad, N)) return;
+    if (no_q && w0 < HD) return;  // q = k = v scheme: the shared vectors are wanted as k and v^T only
 
     // per-thread source rows: chunk ch = tid + 256*u -> row ch/8, k-chunk ch%8
     const int kc = tid & 7;
@@ -325,7 +326,7 @@ __global__ __launch_bounds__(64 * WR * WC, (WR * WC) / 4 * (BT == 256 ? 1 : 2))
 void proj_dma_kernel(int Bsz, int N, int Npad, int D, int H, int d, const bf16_t* __restrict__ X,
                      const bf16_t* __restrict__ Wq, const bf16_t* __restrict__ Wk, const bf16_t* __restrict__ Wv,
                      h16_t* __restrict__ qo, h16_t* __restrict__ ko, h16_t* __restrict__ vto, int tiles_x,
-                     int tiles_w, float qscale, const int* __restrict__ lens, bool skip_q_rows,
+                     int tiles_w, float qscale, const int* __restrict__ lens, bool skip_q_rows, bool no_q,
                      unsigned long long* __restrict__ counters)
 {
     constexpr int NW = WR * WC;
@@ -364,6 +365,7 @@ void proj_dma_kernel(int Bsz, int N, int Npad, int D, int H, int d, const bf16_t
     // padding): their k and v rows are not computed.  (q rows are: every query row has an output.)
     // With padded rows left out as queries too, the same holds for their q rows.
     if (lens != nullptr && (w0 >= HD || skip_q_rows) && past_key_length(lens, x0, Npad, N)) return;
+    if (no_q && w0 < HD) return;  // q = k = v scheme: the shared vectors are wanted as k and v^T only
 
     // The weights stay in the caller's layout, W[k][column]: this tile's columns of the one matrix
     // it lies in.
@@ -698,7 +700,7 @@ hipError_t launch_dma(const Problem& pb, const bf16_t* X, const bf16_t* Wq, cons
     const int grid = ((tiles_x * tiles_w + 7) / 8) * 8;
     hipLaunchKernelGGL((proj_dma_kernel<BT, WR, WC>), dim3(grid), dim3(64 * WR * WC), 0, s, pb.B, pb.N, pb.Npad, pb.D,
                        pb.H, pb.d, X, Wq, Wk, Wv, q, k, vt, tiles_x, tiles_w, qscale, pb.noskip ? nullptr : pb.lens,
-                       pb.skip_rows, pb.counters);
+                       pb.skip_rows, pb.scheme == SCHEME_SYMMETRIC, pb.counters);
     return hipGetLastError();
 }
 
@@ -711,7 +713,8 @@ hipError_t launch_bt(const Problem& pb, const bf16_t* X, const bf16_t* Wt, h16_t
     const int tiles_w = 3 * pb.H * pb.d / BT;
     const int grid = ((tiles_x * tiles_w + 7) / 8) * 8;
     hipLaunchKernelGGL(proj_mfma_kernel<BT>, dim3(grid), dim3(256), 0, s, pb.B, pb.N, pb.Npad, pb.D, pb.H, pb.d, X, Wt,
-                       q, k, vt, tiles_x, tiles_w, qscale, pb.noskip ? nullptr : pb.lens, pb.skip_rows);
+                       q, k, vt, tiles_x, tiles_w, qscale, pb.noskip ? nullptr : pb.lens, pb.skip_rows,
+                       pb.scheme == SCHEME_SYMMETRIC);
     return hipGetLastError();
 }
 

@@ -61,6 +61,21 @@ def expected_phys_blocks(w, scheme, lens=None, skip_padded_rows=False, block=32)
     return total * w.n_heads
 
 
+def expected_sym_blocks(w, tile=128, block=32):
+    """q = k = v scheme on the matrix cores: 32 x 32 score blocks computed when every unordered pair
+    of 128-row tiles is computed once (Eq. (4): the other orientation reuses it), counting the
+    blocks that hold a row and a key below n."""
+    n = w.n
+    nt = (n + tile - 1) // tile
+    total = 0
+    for a in range(nt):
+        row_blocks = len([r for r in range(tile // block) if a * tile + r * block < n])
+        for b in range(a + 1):
+            key_blocks = len([c for c in range(tile // block) if b * tile + c * block < n])
+            total += row_blocks * key_blocks
+    return total * w.batch * w.n_heads
+
+
 def default_scale(w, scale):
     return (1.0 / math.sqrt(w.d_k)) if scale == 0.0 else scale
 

@@ -110,6 +110,25 @@ def test_mfma_path_small(shape, scheme, tiles, seed0):
     _run_and_compare(w, scheme, 0.0, lens=np.zeros(B, dtype=np.int32), flags=tiles)
 
 
+# ---- q = k = v scheme on the matrix cores: each score tile computed once, used for both row blocks ----
+@pytest.mark.parametrize("shape", [
+    # B, n, D, H, d, p
+    (2, 1100, 64, 2, 64, 275),     # 9 tiles, the last one ragged; odd number of ring partitions
+    (1, 1024, 128, 2, 128, 128),   # whole tiles, even partitions (middle diagonal scheduled twice)
+    (3, 200, 64, 2, 64, 25),       # two tiles, second nearly empty
+    (1, 96, 64, 2, 128, 12),       # a single tile: nothing to reuse
+])
+def test_symmetric_on_matrix_cores(shape):
+    B, n, D, H, d, p = shape
+    w = hp.custom_workload("sym_mfma", B, n, D, H, d, p, "bf16", SYM, 2300 + n)
+    err, stats = _run_and_compare(w, SYM, 0.0)
+    assert (stats["phys_br"], stats["phys_bc"]) == (32, 32) and stats["proj_gemms"] == 2
+    assert stats["phys_tiles_executed"] == hp.expected_sym_blocks(w)
+    half = p * (p + 1) // 2 if p % 2 else p * (p + 2) // 2      # Sec. 4.2, on the tile matrix
+    assert stats["tiles_executed"] == B * H * half
+    _run_and_compare(w, SYM, 1.0 / 32)
+
+
 # ---- row maxima that move along the walk: the running reference of Eq. (2)'s online form ----------
 @pytest.mark.parametrize("profile", ["ramp", "steps"])
 @pytest.mark.parametrize("scheme", [FULL, CAUSAL])
