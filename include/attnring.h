@@ -74,7 +74,13 @@ enum { ATTN_FLAG_NO_SKIP = 1u,
         * their q rows are not projected, and the counts are those of the len x len problems.
         * (Sec. 5.1's rule - what is masked is not computed - applied to both sides of a pair.)
         * No effect without key lengths. */
-       ATTN_FLAG_SKIP_PADDED_ROWS = 8u };
+       ATTN_FLAG_SKIP_PADDED_ROWS = 8u,
+       /* Matrix-core path: the query vectors are projected inside the attention kernel, by each
+        * wavefront for its own rows, and never leave the registers; the projection kernel computes
+        * k and v only.  (Sec. 3.1 / 4.1: the inputs of a row block are loaded once and used for all
+        * phases.)  Needs d_model a multiple of 64 and 16-byte aligned weights, else it has no effect;
+        * no effect on ATTN_SCHEME_SYMMETRIC and on the float path.  Results obey the same bars. */
+       ATTN_FLAG_FUSE_Q_PROJECTION = 16u };
 
 typedef struct {
     int32_t batch;     /* >= 1 */

@@ -21,6 +21,7 @@ ATTN_FLAG_NO_SKIP = 1
 ATTN_FLAG_WIDE_TILES = 2
 ATTN_FLAG_NARROW_TILES = 4
 ATTN_FLAG_SKIP_PADDED_ROWS = 8
+ATTN_FLAG_FUSE_Q_PROJECTION = 16
 
 EXPORTS = ("attn_init", "attn_set_key_lengths", "attn_forward", "attn_forward_static", "attn_stats",
            "attn_profile", "attn_profile_read", "attn_last_error", "attn_destroy")

@@ -48,6 +48,16 @@
 namespace attnring {
 namespace {
 
+// f(integral_constant<int, 0>) ... f(integral_constant<int, N - 1>)
+template <int N, class F, int I = 0>
+__device__ __forceinline__ void static_for_q(F&& f)
+{
+    if constexpr (I < N) {
+        f(std::integral_constant<int, I>{});
+        static_for_q<N, F, I + 1>(static_cast<F&&>(f));
+    }
+}
+
 constexpr float PIPE_RAISE = 8.f;  // slack of the lazy reference, in base-2 exponent units
 
 template <int DK, int WAVES, bool CAUSAL>
@@ -215,11 +225,144 @@ struct Pipe {
     }
 };
 
-template <int DK, int WAVES, bool CAUSAL>
+// q' = (x.Wq) * qscale for the 32 rows of a wavefront (lane L: row L % 32), as B operands of the score
+// MFMAs: qf[ks] holds 8 consecutive columns 16 ks + 8 (L / 32) ...  All wavefronts of the workgroup
+// call it together (same head): the weight columns of the head go through LDS in slices of 64 rows
+// of Wq, two buffers at wbuf (2 * 64 * d_k * 2 bytes), one barrier per slice; what a slice needs from
+// global memory (its part of Wq, the lane's 128 bytes of x) is requested four slices ahead.
+//   Q^T [d_k x 32 rows] += Wq_h^T [d_k x 16] . x^T [16 x 32 rows]   per k-step, bf16 MFMA, fp32 sums:
+//   A operand: a column of Wq (one l) along 8 consecutive k - read from the k-major LDS slice with
+//              the transposing 64-bit read (16 lanes hand in a 4 k x 16 columns patch, lane i gets
+//              column i); rows of 128 bytes (d_k = 64) have their chunks XOR-ed with 4*((k>>1)&1),
+//              rows of 256 bytes with 4*(k&3), so the four k-rows of a patch meet different banks;
+//   B operand: 16 bytes of the lane's own row of x, straight from global memory.
+// xrow: the lane's row of x; wh: Wq at the first column of the head, row pitch hd; d_model % 64 == 0.
+template <int DK, int WAVES>
+__device__ __forceinline__ void project_queries(u32x4 (&qf)[DK / 16], const bf16_t* __restrict__ xrow,
+                                                const bf16_t* __restrict__ wh, int d_model, int hd, float qscale,
+                                                unsigned char* wbuf, int tid, int lane)
+{
+    constexpr int NDB = DK / 32, NKS = DK / 16;
+    constexpr int SLK = 64, KSS = SLK / 16;  // rows of Wq and k-steps per slice
+    constexpr int WROWB = DK * 2, CPRW = DK / 8, NCH = SLK * CPRW, NT = 64 * WAVES;
+    constexpr int PER = (NCH + NT - 1) / NT;  // 16-byte chunks of a slice per thread
+    constexpr int SLICE = SLK * WROWB;
+    constexpr int AHEAD = 4;
+    // Everything below depends on the lane only.  Taken from opaque copies of the thread and lane
+    // numbers it is computed here, in every pass; otherwise the compiler hoists two dozen addresses
+    // out of the pass loop and keeps them in scratch memory during the walk.
+    asm volatile("" : "+v"(tid), "+v"(lane));
+    const int g = lane >> 5;
+    auto wswz = [](int kr) { return DK == 64 ? 4 * ((kr >> 1) & 1) : 4 * (kr & 3); };
+    f32x16 qa[NDB];
+#pragma unroll
+    for (int db = 0; db < NDB; ++db)
+#pragma unroll
+        for (int e = 0; e < 16; ++e) qa[db][e] = 0.f;
+    // this lane's address of the transposing reads: k-step 0 of a slice, first read; the k-steps of a
+    // slice lie 16 rows apart, which leaves the swizzle alone
+    const unsigned lds_w = (unsigned)(size_t)(__attribute__((address_space(3))) unsigned char*)wbuf;
+    unsigned wfo[NDB];
+    {
+        const int i16 = lane & 15;
+        const int kr = 8 * g + (i16 >> 2);
+#pragma unroll
+        for (int db = 0; db < NDB; ++db) {
+            const int col = db * 32 + 16 * ((lane >> 4) & 1) + 4 * (i16 & 3);
+            wfo[db] = (unsigned)(kr * WROWB + (((col >> 3) ^ wswz(kr)) << 4) + ((col & 7) << 1));
+        }
+    }
+    u32x4 wreg[AHEAD][PER], xreg[AHEAD][KSS];
+    auto fetch = [&](int sl, auto set_) {
+        constexpr int SET = decltype(set_)::value;
+#pragma unroll
+        for (int u = 0; u < PER; ++u) {
+            const int c = tid + NT * u;
+            if (c < NCH) wreg[SET][u] = *(const u32x4*)(wh + (size_t)(SLK * sl + c / CPRW) * hd + (c % CPRW) * 8);
+        }
+#pragma unroll
+        for (int ks = 0; ks < KSS; ++ks) xreg[SET][ks] = *(const u32x4*)(xrow + SLK * sl + 16 * ks + 8 * g);
+    };
+    auto stage = [&](int buf, auto set_) {
+        constexpr int SET = decltype(set_)::value;
+#pragma unroll
+        for (int u = 0; u < PER; ++u) {
+            const int c = tid + NT * u;
+            if (c < NCH) {
+                const int kr = c / CPRW, p = c % CPRW;
+                *(u32x4*)(wbuf + buf * SLICE + kr * WROWB + ((p ^ wswz(kr)) << 4)) = wreg[SET][u];
+            }
+        }
+    };
+    const int ns = d_model / SLK;
+    // slice sl: Wq part in LDS buffer sl & 1 (staged during slice sl - 1), x in register set sl % AHEAD
+    auto slice = [&](int sl, auto set_) {
+        constexpr int SET = decltype(set_)::value;
+        if (sl >= ns) return;
+        const unsigned base = lds_w + (unsigned)((sl & 1) * SLICE);
+        // the fragments of GRP k-steps are requested in one run and awaited once
+        constexpr int GRP = KSS / 2;
+#pragma unroll
+        for (int k0 = 0; k0 < KSS; k0 += GRP) {
+            u32x4 af[GRP][NDB];
+#pragma unroll
+            for (int kk = 0; kk < GRP; ++kk)
+#pragma unroll
+                for (int db = 0; db < NDB; ++db) {
+                    u32x2 lo, hi;
+                    asm volatile("ds_read_b64_tr_b16 %0, %1 offset:%2"
+                                 : "=v"(lo)
+                                 : "v"(base + wfo[db]), "n"(16 * (k0 + kk) * WROWB));
+                    asm volatile("ds_read_b64_tr_b16 %0, %1 offset:%2"
+                                 : "=v"(hi)
+                                 : "v"(base + wfo[db]), "n"((16 * (k0 + kk) + 4) * WROWB));
+                    af[kk][db] = u32x4{lo[0], lo[1], hi[0], hi[1]};
+                }
+            __builtin_amdgcn_sched_barrier(0);
+            __builtin_amdgcn_s_waitcnt(0xC07F);  // the compiler does not count hand-written LDS reads
+            __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+            for (int kk = 0; kk < GRP; ++kk)
+#pragma unroll
+                for (int db = 0; db < NDB; ++db) qa[db] = mfma32(af[kk][db], xreg[SET][k0 + kk], qa[db]);
+        }
+        // the other buffer was last read in slice sl - 1, which every wavefront has left
+        if (sl + 1 < ns) stage((sl + 1) & 1, std::integral_constant<int, (SET + 1) % AHEAD>{});
+        if (sl + AHEAD < ns) fetch(sl + AHEAD, set_);
+        __syncthreads();
+    };
+    static_for_q<AHEAD>([&](auto j_) { if (decltype(j_)::value < ns) fetch(decltype(j_)::value, j_); });
+    stage(0, std::integral_constant<int, 0>{});
+    __syncthreads();
+#pragma nounroll
+    for (int sl = 0; sl < ns; sl += AHEAD)
+        static_for_q<AHEAD>([&](auto j_) { slice(sl + decltype(j_)::value, j_); });
+    // Accumulator layout -> operand layout.  For k-step ks the lane holds, of the 16 columns,
+    // {4g .. 4g+3} and {8+4g .. 8+4g+3}; the operand wants {8g .. 8g+7}: the halves of the wavefront
+    // exchange one group of four.
+#pragma unroll
+    for (int ks = 0; ks < NKS; ++ks) {
+        const int db = ks >> 1, hh = ks & 1;
+        unsigned w[4];
+#pragma unroll
+        for (int j = 0; j < 4; ++j)
+            w[j] = pack_f16_sat(qa[db][8 * hh + 2 * j] * qscale, qa[db][8 * hh + 2 * j + 1] * qscale);
+        const unsigned s0 = g ? w[0] : w[2], s1 = g ? w[1] : w[3];
+        const unsigned r0 = __shfl_xor(s0, 32, 64), r1 = __shfl_xor(s1, 32, 64);
+        qf[ks] = g ? u32x4{r0, r1, w[2], w[3]} : u32x4{w[0], w[1], r0, r1};
+    }
+}
+
+// FUSEQ: the query vectors are not read from the workspace but projected here, q = x.Wq (Sec. 3.1),
+// by each wavefront for its own 32 rows in the prologue of a pass, and stay in registers: the
+// inputs of the row block are loaded once and used for all three phases (the aim of Sec. 3.1 and
+// 4.1), and the projection kernel in front computes k and v only.
+template <int DK, int WAVES, bool CAUSAL, bool FUSEQ>
 __global__ __launch_bounds__(64 * WAVES)
 __attribute__((amdgpu_waves_per_eu(Pipe<DK, WAVES, CAUSAL>::OCC, Pipe<DK, WAVES, CAUSAL>::OCC)))
 void attn_pipe_kernel(Problem pb, CountCfg cc, const h16_t* __restrict__ q, const h16_t* __restrict__ k,
-                      const h16_t* __restrict__ vt, bf16_t* __restrict__ out, int n_qtiles, int per_head, int n_work)
+                      const h16_t* __restrict__ vt, bf16_t* __restrict__ out, int n_qtiles, int per_head, int n_work,
+                      const bf16_t* __restrict__ X, const bf16_t* __restrict__ Wq, float qscale)
 {
     typedef Pipe<DK, WAVES, CAUSAL> T;
     constexpr int NKS = T::NKS, NDB = T::NDB, BR = T::BR;
@@ -367,8 +510,10 @@ void attn_pipe_kernel(Problem pb, CountCfg cc, const h16_t* __restrict__ q, cons
         if (nT > 0) {
             // Q rows of this wavefront as B operands (rows >= n of the workspace are zero).
             u32x4 qf[NKS];
+            if constexpr (!FUSEQ) {
 #pragma unroll
-            for (int ks = 0; ks < NKS; ++ks) qf[ks] = *(const u32x4*)(qh + (size_t)i * DK + ks * 16 + g * 8);
+                for (int ks = 0; ks < NKS; ++ks) qf[ks] = *(const u32x4*)(qh + (size_t)i * DK + ks * 16 + g * 8);
+            }
 
             // Piece c (K pieces first) of the tile with K at byte ksoff and V^T at byte vsoff of the
             // head, into the stage at LDS byte `stage`.  A buffer load: descriptor base, the lane's
@@ -428,6 +573,11 @@ void attn_pipe_kernel(Problem pb, CountCfg cc, const h16_t* __restrict__ q, cons
             {
                 const int pre = nT < T::STAGES - 1 ? nT : T::STAGES - 1;
                 for (int u = 0; u < pre; ++u) issue_tile(u);
+                // the last stage of the ring is free until the first barrier: the weight slices of
+                // the query projection pass through it while the first tiles are on their way
+                if constexpr (FUSEQ)
+                    project_queries<DK, WAVES>(qf, X + ((size_t)bb * N + (i < N ? i : N - 1)) * pb.D, Wq + (size_t)h * DK,
+                                               pb.D, pb.H * DK, qscale, lds + (T::STAGES - 1) * T::STAGE, tid, lane);
                 tile_sync(0, false);
             }
             // The barrier of tile t (t >= 1) lies in front of E(2t) for group 0 and between E(2t) and
@@ -605,9 +755,11 @@ void attn_pipe_kernel(Problem pb, CountCfg cc, const h16_t* __restrict__ q, cons
 }  // namespace
 
 hipError_t launch_attn_pipe(const Problem& pb, const h16_t* q, const h16_t* k, const h16_t* vt, bf16_t* out,
-                            int waves, hipStream_t s)
+                            int waves, hipStream_t s, const bf16_t* X, const bf16_t* Wq)
 {
     const bool causal = pb.scheme == SCHEME_CAUSAL;
+    const bool fuse = X != nullptr && Wq != nullptr;  // queries projected inside the kernel
+    const float qscale = pb.scale * 1.4426950408889634f;
     const int br = 32 * waves;
     const int n_qtiles = (pb.N + br - 1) / br;
     const int per_head = causal ? (n_qtiles + 1) / 2 : n_qtiles;
@@ -618,13 +770,19 @@ hipError_t launch_attn_pipe(const Problem& pb, const h16_t* q, const h16_t* k, c
     cc.b_shift = -1;
     for (int sft = 0; sft < 31; ++sft)
         if ((1 << sft) == pb.b) cc.b_shift = sft;
-#define ATTN_LAUNCH(DK_, W_, C_)                                                                                     \
-    hipLaunchKernelGGL((attn_pipe_kernel<DK_, W_, C_>), dim3(grid), dim3(64 * W_), 0, s, pb, cc, q, k, vt, out, \
-                       n_qtiles, per_head, n_work)
-    if (pb.d == 64 && waves == 4) { if (causal) ATTN_LAUNCH(64, 4, true); else ATTN_LAUNCH(64, 4, false); }
-    else if (pb.d == 64 && waves == 8) { if (causal) ATTN_LAUNCH(64, 8, true); else ATTN_LAUNCH(64, 8, false); }
-    else if (pb.d == 128 && waves == 8) { if (causal) ATTN_LAUNCH(128, 8, true); else ATTN_LAUNCH(128, 8, false); }
+#define ATTN_LAUNCH(DK_, W_, C_, F_)                                                                                    \
+    hipLaunchKernelGGL((attn_pipe_kernel<DK_, W_, C_, F_>), dim3(grid), dim3(64 * W_), 0, s, pb, cc, q, k, vt, out, \
+                       n_qtiles, per_head, n_work, X, Wq, qscale)
+#define ATTN_PICK(DK_, W_)                                                                  \
+    do {                                                                                    \
+        if (causal) { if (fuse) ATTN_LAUNCH(DK_, W_, true, true); else ATTN_LAUNCH(DK_, W_, true, false); }   \
+        else { if (fuse) ATTN_LAUNCH(DK_, W_, false, true); else ATTN_LAUNCH(DK_, W_, false, false); }        \
+    } while (0)
+    if (pb.d == 64 && waves == 4) ATTN_PICK(64, 4);
+    else if (pb.d == 64 && waves == 8) ATTN_PICK(64, 8);
+    else if (pb.d == 128 && waves == 8) ATTN_PICK(128, 8);
     else return hipErrorInvalidValue;
+#undef ATTN_PICK
 #undef ATTN_LAUNCH
     return hipGetLastError();
 }

@@ -87,6 +87,7 @@ Problem make_problem(const attn_ctx* c, int scheme)
     pb.P = c->cfg.p; pb.b = c->b; pb.Npad = c->Npad; pb.scale = c->scale; pb.scheme = scheme;
     pb.noskip = (c->cfg.flags & ATTN_FLAG_NO_SKIP) != 0;
     pb.skip_rows = (c->cfg.flags & ATTN_FLAG_SKIP_PADDED_ROWS) != 0 && c->lens != nullptr;
+    pb.no_q = scheme == ATTN_SCHEME_SYMMETRIC;
     pb.is_bf16 = c->cfg.dtype == ATTN_BF16;
     pb.lens = c->lens;
     pb.counters = c->counters;
@@ -181,7 +182,7 @@ attn_status validate_config(const attn_config* cfg)
     if (cfg->dtype != ATTN_F32 && cfg->dtype != ATTN_BF16)
         return fail(nullptr, ATTN_ERR_INVALID, "attn config: unknown dtype%s");
     if (cfg->flags & ~(uint32_t)(ATTN_FLAG_NO_SKIP | ATTN_FLAG_WIDE_TILES | ATTN_FLAG_NARROW_TILES |
-                                 ATTN_FLAG_SKIP_PADDED_ROWS))
+                                 ATTN_FLAG_SKIP_PADDED_ROWS | ATTN_FLAG_FUSE_Q_PROJECTION))
         return fail(nullptr, ATTN_ERR_INVALID, "attn config: unknown flag%s");
     if ((cfg->flags & ATTN_FLAG_WIDE_TILES) && (cfg->flags & ATTN_FLAG_NARROW_TILES))
         return fail(nullptr, ATTN_ERR_INVALID, "attn config: WIDE_TILES and NARROW_TILES exclude each other%s");
@@ -379,6 +380,10 @@ attn_status attn_forward(attn_ctx* ctx, const void* X, const void* Wq, const voi
             MARK(1);
             prepared = true;
         }
+        // queries projected inside the attention kernel: when asked for and the weights are read in place
+        const bool fuse_q = !sym && (cf.flags & ATTN_FLAG_FUSE_Q_PROJECTION) != 0 &&
+                            proj_reads_weights_in_place(pb, (const bf16_t*)Wq, (const bf16_t*)Wk, (const bf16_t*)Wv);
+        if (fuse_q) pb.no_q = true;
         e = launch_proj_mfma(pb, (const bf16_t*)X, (const bf16_t*)Wq, (const bf16_t*)Wk, (const bf16_t*)Wv, ctx->wt,
                              ctx->qb, ctx->kb, ctx->vtb, s);
         CHECK("launch proj_mfma");
@@ -391,7 +396,8 @@ attn_status attn_forward(attn_ctx* ctx, const void* X, const void* Wq, const voi
             // d_k = 64: 128-row workgroups of 4 wavefronts, three of them per CU; d_k = 128: 256 rows, 8 wavefronts
             int waves = cf.d_k == 128 ? 8 : 4;
             if (cf.d_k == 64 && (cf.flags & ATTN_FLAG_WIDE_TILES)) waves = 8;
-            e = launch_attn_pipe(pb, ctx->qb, ctx->kb, ctx->vtb, (bf16_t*)out, waves, s);
+            e = launch_attn_pipe(pb, ctx->qb, ctx->kb, ctx->vtb, (bf16_t*)out, waves, s,
+                                 fuse_q ? (const bf16_t*)X : nullptr, fuse_q ? (const bf16_t*)Wq : nullptr);
             CHECK("launch attention (mfma)");
             ctx->last_proj_gemms = 3;
         }
@@ -464,6 +470,7 @@ attn_status attn_forward_static(const attn_config* cfg, const int32_t* lens_dev,
     pb.scheme = scheme;
     pb.noskip = (cfg->flags & ATTN_FLAG_NO_SKIP) != 0;
     pb.skip_rows = (cfg->flags & ATTN_FLAG_SKIP_PADDED_ROWS) != 0 && lens_dev != nullptr;
+    pb.no_q = false;
     pb.is_bf16 = true;
     pb.lens = lens_dev;
     if (!matrix_core_shape(cfg) || !aligned_to(X, 16) || !aligned_to(out, 8) ||

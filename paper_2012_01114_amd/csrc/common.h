@@ -21,6 +21,7 @@ struct Problem {
     int scheme;
     bool noskip;         // debug: visit every tile, mask with -inf
     bool skip_rows;      // with key lengths: rows i >= len take part in no pair and give zeros
+    bool no_q;           // the projection kernel leaves q out (q = k = v scheme; queries projected by the attention kernel)
     bool is_bf16;        // storage type of X, W, out
     const int* lens;     // device, [B] or nullptr
     unsigned long long* counters;  // device: CNT_SLOTS slots of (logical tiles, physical score blocks), then totals
@@ -64,8 +65,10 @@ hipError_t launch_proj_mfma(const Problem& pb, const bf16_t* X, const bf16_t* Wq
                             const bf16_t* Wv, const bf16_t* Wt, h16_t* q, h16_t* k, h16_t* vt, hipStream_t s);
 // Fused phases 1-3 with redundant blocks left out; `waves` wavefronts of 32 rows per workgroup:
 // 4 or 8 for d_k = 64, 8 for d_k = 128.
+// X and Wq given: the kernel projects its queries itself (q is not read).
 hipError_t launch_attn_pipe(const Problem& pb, const h16_t* q, const h16_t* k, const h16_t* vt,
-                            bf16_t* out, int waves, hipStream_t s);
+                            bf16_t* out, int waves, hipStream_t s, const bf16_t* X = nullptr,
+                            const bf16_t* Wq = nullptr);
 // q = k = v scheme on the matrix cores: every 128 x 128 score tile computed once and used for both
 // of its row blocks, partial row states merged by a second kernel.  z, zt: the shared vectors in
 // the k and v^T layouts above; work: sym_pair_workspace_floats(pb) floats.

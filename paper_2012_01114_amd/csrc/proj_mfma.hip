@@ -124,10 +124,10 @@ __device__ __forceinline__ void tile_of(int id, int tiles_x, int tiles_w, int& t
 // Both tile indices are therefore permuted, so that every run holds q, k and v tiles in equal
 // parts (groups of three column tiles, dealt round-robin over the three matrices) and x tiles
 // from all over the batch (a multiplier that is coprime to their number).
-__device__ __forceinline__ void spread_tiles(int tiles_x, int tiles_w, int& tw, int& tx)
+__device__ __forceinline__ void spread_tiles(int tiles_x, int tiles_w, int& tw, int& tx, int n_matrices = 3)
 {
-    const int per_matrix = tiles_w / 3;
-    tw = (tw % 3) * per_matrix + tw / 3;
+    const int per_matrix = tiles_w / n_matrices;
+    tw = (tw % n_matrices) * per_matrix + tw / n_matrices;
     int mult = tiles_x / 8 + 1;
     while (true) {  // the next number coprime to tiles_x
         int a = mult, b = tiles_x;
@@ -357,15 +357,16 @@ void proj_dma_kernel(int Bsz, int N, int Npad, int D, int H, int d, const bf16_t
     const int tile_id = (blockIdx.x & 7) * per_xcd + (blockIdx.x >> 3);
     if (tile_id >= n_tiles) return;
     int tw, tx_;
-    tile_of(tile_id, tiles_x, tiles_w, tw, tx_, lens != nullptr ? 3 : GROUP_W);
-    if (lens != nullptr) spread_tiles(tiles_x, tiles_w, tw, tx_);
-    const int x0 = tx_ * BT, w0 = tw * BT;
+    // no_q (the queries are not wanted: q = k = v scheme, or projected by the attention kernel): the
+    // grid holds the k and v column tiles only
+    tile_of(tile_id, tiles_x, tiles_w, tw, tx_, lens != nullptr ? (no_q ? 2 : 3) : GROUP_W);
+    if (lens != nullptr) spread_tiles(tiles_x, tiles_w, tw, tx_, no_q ? 2 : 3);
+    const int x0 = tx_ * BT, w0 = tw * BT + (no_q ? HD : 0);
     const bool is_v = w0 >= 2 * HD;
     // Keys past the key length of their batch item are in no allowed pair (Sec. 5.1 applied to
     // padding): their k and v rows are not computed.  (q rows are: every query row has an output.)
     // With padded rows left out as queries too, the same holds for their q rows.
     if (lens != nullptr && (w0 >= HD || skip_q_rows) && past_key_length(lens, x0, Npad, N)) return;
-    if (no_q && w0 < HD) return;  // q = k = v scheme: the shared vectors are wanted as k and v^T only
 
     // The weights stay in the caller's layout, W[k][column]: this tile's columns of the one matrix
     // it lies in.
@@ -696,11 +697,11 @@ hipError_t launch_dma(const Problem& pb, const bf16_t* X, const bf16_t* Wq, cons
 {
     const float qscale = q_prescale(pb);
     const int tiles_x = pb.B * pb.Npad / BT;
-    const int tiles_w = 3 * pb.H * pb.d / BT;
+    const int tiles_w = (pb.no_q ? 2 : 3) * pb.H * pb.d / BT;
     const int grid = ((tiles_x * tiles_w + 7) / 8) * 8;
     hipLaunchKernelGGL((proj_dma_kernel<BT, WR, WC>), dim3(grid), dim3(64 * WR * WC), 0, s, pb.B, pb.N, pb.Npad, pb.D,
                        pb.H, pb.d, X, Wq, Wk, Wv, q, k, vt, tiles_x, tiles_w, qscale, pb.noskip ? nullptr : pb.lens,
-                       pb.skip_rows, pb.scheme == SCHEME_SYMMETRIC, pb.counters);
+                       pb.skip_rows, pb.no_q, pb.counters);
     return hipGetLastError();
 }
 
@@ -713,8 +714,7 @@ hipError_t launch_bt(const Problem& pb, const bf16_t* X, const bf16_t* Wt, h16_t
     const int tiles_w = 3 * pb.H * pb.d / BT;
     const int grid = ((tiles_x * tiles_w + 7) / 8) * 8;
     hipLaunchKernelGGL(proj_mfma_kernel<BT>, dim3(grid), dim3(256), 0, s, pb.B, pb.N, pb.Npad, pb.D, pb.H, pb.d, X, Wt,
-                       q, k, vt, tiles_x, tiles_w, qscale, pb.noskip ? nullptr : pb.lens, pb.skip_rows,
-                       pb.scheme == SCHEME_SYMMETRIC);
+                       q, k, vt, tiles_x, tiles_w, qscale, pb.noskip ? nullptr : pb.lens, pb.skip_rows, pb.no_q);
     return hipGetLastError();
 }
 
@@ -752,7 +752,7 @@ hipError_t launch_proj_mfma(const Problem& pb, const bf16_t* X, const bf16_t* Wq
     // mixes q, k and v columns) and still gives every CU a few tiles.
     const int HD = pb.H * pb.d;
     const long rows = (long)pb.B * pb.Npad;
-    const bool big = HD % 256 == 0 && rows % 256 == 0 && (rows / 256) * (3L * HD / 256) >= 512;
+    const bool big = HD % 256 == 0 && rows % 256 == 0 && (rows / 256) * ((pb.no_q ? 2L : 3L) * HD / 256) >= 512;
     if (proj_reads_weights_in_place(pb, Wq, Wk, Wv)) {  // operands go straight to LDS
         if (big) return launch_dma<256, 2, 4>(pb, X, Wq, Wk, Wv, q, k, vt, s);
         return launch_dma<128, 2, 2>(pb, X, Wq, Wk, Wv, q, k, vt, s);

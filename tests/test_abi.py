@@ -47,7 +47,7 @@ def _init(**kw):
     (dict(n=0), ar.ATTN_ERR_INVALID),
     (dict(batch=-1), ar.ATTN_ERR_INVALID),
     (dict(dtype=7), ar.ATTN_ERR_INVALID),
-    (dict(flags=16), ar.ATTN_ERR_INVALID),
+    (dict(flags=32), ar.ATTN_ERR_INVALID),
     (dict(flags=6), ar.ATTN_ERR_INVALID),
     (dict(scale=float("nan")), ar.ATTN_ERR_INVALID),
     (dict(n=18, p=4), ar.ATTN_ERR_SHAPE),          # n must be divisible by the ring partitions

@@ -110,6 +110,34 @@ def test_mfma_path_small(shape, scheme, tiles, seed0):
     _run_and_compare(w, scheme, 0.0, lens=np.zeros(B, dtype=np.int32), flags=tiles)
 
 
+# ---- queries projected inside the attention kernel (ATTN_FLAG_FUSE_Q_PROJECTION) ----------------------
+@pytest.mark.parametrize("shape", [
+    (2, 320, 64, 2, 64, 40),      # two 32-row slices of Wq
+    (2, 384, 128, 2, 128, 12),    # d_k = 128
+    (1, 1096, 64, 1, 128, 137),   # several 256-row tiles and a ragged tail
+    (1, 264, 192, 2, 64, 33),     # six slices
+    (2, 256, 320, 2, 128, 32),    # ten slices
+    (1, 200, 96, 3, 64, 25),      # d_model not a multiple of 64: the flag has no effect
+])
+@pytest.mark.parametrize("scheme", [FULL, CAUSAL])
+@pytest.mark.parametrize("tiles", [ar.ATTN_FLAG_NARROW_TILES, ar.ATTN_FLAG_WIDE_TILES])
+def test_queries_projected_in_the_attention_kernel(shape, scheme, tiles):
+    B, n, D, H, d, p = shape
+    w = hp.custom_workload("fuse_q", B, n, D, H, d, p, "bf16", scheme, 3100 + n)
+    flags = tiles | ar.ATTN_FLAG_FUSE_Q_PROJECTION
+    _run_and_compare(w, scheme, 0.0, flags=flags)
+    lens = np.random.default_rng(n + 2).integers(1, n + 1, B).astype(np.int32)
+    lens[-1] = n // 2 + 3
+    _run_and_compare(w, scheme, 0.0, lens=lens, flags=flags)
+    _run_and_compare(w, scheme, 0.0, lens=np.zeros(B, dtype=np.int32), flags=flags)
+
+
+def test_causal_workload_with_queries_projected_in_the_attention_kernel():
+    w = inputs.WORKLOADS["causal"]
+    err, stats = _run_and_compare(w, w.scheme, 0.0, flags=ar.ATTN_FLAG_FUSE_Q_PROJECTION)
+    assert stats["tiles_executed"] == 96 * 8256
+
+
 # ---- q = k = v scheme on the matrix cores: each score tile computed once, used for both row blocks ----
 @pytest.mark.parametrize("shape", [
     # B, n, D, H, d, p
