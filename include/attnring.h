@@ -29,8 +29,17 @@
  *     [d_model][n_heads*d_k] (q = x.W, head h uses columns h*d_k ..); out
  *     [batch][n][n_heads*d_k]; elements are float or bfloat16 per cfg.dtype;
  *     accumulation is always float.
- *   - attn_forward only enqueues work on the given stream and does not wait for it.
+ *   - attn_forward only enqueues work on the given stream and does not wait for it, with one
+ *     exception: the first call on a context that needs a workspace attn_init did not allocate
+ *     allocates it with hipMalloc, which synchronises the device.  That is the float workspace when
+ *     a context whose shape fits the matrix-core kernels is given unaligned pointers, and the
+ *     workspace of ATTN_SCHEME_SYMMETRIC (score matrix on the float path, partial row states on the
+ *     matrix-core path).  Every later call with the same kind of work only enqueues.
  *     One context serves one call at a time (calls on it are ordered by the caller).
+ *   - bfloat16 storage: the matrix-core kernels (d_k 64 or 128, d_model a multiple of 8) contract
+ *     bfloat16 operands in the projection and keep the projected q, k, v and the exponentials in half
+ *     precision (same matrix-core rate, three more significand bits; values beyond its range
+ *     saturate), with float accumulation throughout; out is rounded once to bfloat16.
  */
 #ifndef ATTNRING_H
 #define ATTNRING_H
@@ -104,7 +113,8 @@ typedef struct {
     uint64_t pairs_executed;      /* tiles_executed * (n/p)^2 */
     uint64_t phys_tiles_executed; /* score blocks of phys_br x phys_bc pairs the kernels issued; device-counted */
     int32_t phys_br, phys_bc;
-    uint64_t proj_gemms;          /* 3, or 1 for the q = k = v scheme (0 when X is used unprojected) */
+    uint64_t proj_gemms;          /* 3; q = k = v scheme: 1 on the float path (0 when X is used unprojected),
+                                     2 on the matrix-core path (z = x.Wq produced in two layouts) */
 } attn_stats_t;
 
 typedef struct {
@@ -139,9 +149,12 @@ attn_status attn_set_key_lengths(attn_ctx* ctx, const int32_t* lens_dev);
  * stream): projections, scores, softmax and weighted sum, skipping what `scheme`
  * makes redundant (Sec. 3-5; see the head of this file).  For
  * ATTN_SCHEME_SYMMETRIC the shared vectors are z = x.Wq; Wk and Wv are ignored
- * (may be NULL); Wq == NULL means z = x and needs d_model == n_heads*d_k.  The
- * symmetric scheme keeps one head's score matrix per (batch, head) in device
- * memory and is refused (UNSUPPORTED) above 1 GiB of it.
+ * (may be NULL); Wq == NULL means z = x and needs d_model == n_heads*d_k.  On the
+ * matrix-core path (bfloat16, d_k 64 or 128, Wq given) every 128 x 128 score tile is
+ * computed once and used for both of its row blocks (Sec. 4.1, Eq. (4)), the scores stay
+ * on chip and 128 (d_k + 2) floats of partial row state per use go through device memory;
+ * elsewhere one score matrix per (batch, head) does.  Either workspace is bounded by
+ * 1 GiB; a shape beyond it on both paths is refused (UNSUPPORTED).
  * Errors: INVALID (NULL ctx/X/out, NULL weights where needed, bad scheme),
  * UNSUPPORTED, ALLOC, DEVICE (launch failure).
  */
@@ -150,8 +163,9 @@ attn_status attn_forward(attn_ctx* ctx, const void* X, const void* Wq, const voi
 
 /*
  * Wait for the stream of the last attn_forward and report its executed-versus-full
- * counts.  The closed-form fields are evaluated on the host (key lengths are
- * copied back for that); the *_executed fields are what the kernels counted.
+ * counts.  The closed-form fields are evaluated on the host with the key lengths that
+ * call ran with (they are copied back for that: the array it was given must still be
+ * valid); the *_executed fields are what the kernels counted.
  */
 attn_status attn_stats(attn_ctx* ctx, attn_stats_t* out);
 
