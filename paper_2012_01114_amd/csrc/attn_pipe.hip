@@ -59,6 +59,9 @@ __device__ __forceinline__ void static_for_q(F&& f)
 }
 
 constexpr float PIPE_RAISE = 8.f;  // slack of the lazy reference, in base-2 exponent units
+// A lane's 16 exponentials of a block add up to more than this only if one of them is above
+// 2^PIPE_RAISE, and as long as they do not, none is above 2^12, far inside half precision.
+constexpr float PIPE_SUM_LIMIT = 4096.f;
 
 template <int DK, int WAVES, bool CAUSAL>
 struct Pipe {
@@ -199,8 +202,9 @@ struct Pipe {
     // Phase 2 (Eq. (2)) of the block in r.S; the row sum is normalised at the very end.
     // SHIFT: the scores still refer to a reference that was `delta` lower.
     // `between(p)` runs behind score pair p (0..7): the LDS requests for the matrix phase.
+    // Returns the sum of the lane's 16 exponentials, which the caller adds to r.l.
     template <bool SHIFT, class F>
-    static __device__ __forceinline__ void exponentials(Row& r, float delta, F&& between)
+    static __device__ __forceinline__ float exponentials(Row& r, float delta, F&& between)
     {
         // The row sum is taken with plain additions of the unrounded exponentials.  A v_dot2c on
         // the rounded pairs would be half the instructions, but dot instructions do not run beside
@@ -208,7 +212,7 @@ struct Pipe {
         // whichever wavefront they are, which serialises the vector phase with the matrix phase
         // of the wavefront it shares the SIMD with (measured: an MFMA followed by one v_dot2c
         // takes 51 cycles instead of 32; exponentials, conversions, max and fma add 1-3).
-        float psum0 = r.l, psum1 = 0.f;
+        float psum0 = 0.f, psum1 = 0.f;
 #pragma unroll
         for (int hf = 0; hf < 2; ++hf)
 #pragma unroll
@@ -221,7 +225,7 @@ struct Pipe {
                 psum1 += p1;
                 between(4 * hf + w);
             }
-        r.l = psum0 + psum1;
+        return psum0 + psum1;
     }
 };
 
@@ -620,14 +624,21 @@ void attn_pipe_kernel(Problem pb, CountCfg cc, const h16_t* __restrict__ q, cons
                 int lim_base = len - 1;  // the lane's last allowed key
                 if (CAUSAL) lim_base = lim_base < i ? lim_base : i;
                 if (i >= rlen) lim_base = -1;  // a row that is left out has no allowed key
+                const bool live = lim_base >= 0;
+                bool fresh = true;  // a live row may still be without a reference
                 lim_base -= 4 * g;
 
                 // E(n) for the upper (UPPER = 1: first block of a tile) or lower 32 keys of tile t
                 auto phase_e = [&](auto upper, bool masked, int J) {
                     constexpr int UPPER = decltype(upper)::value;
                     if (masked) T::mask_block(r.S, lim_base - (J * BC + 32 * UPPER));
-                    const float mxl = T::USE_CNEG ? T::max16(r.S) : T::max16(r.S) - r.mref;
-                    if (__builtin_amdgcn_ballot_w64(mxl > r.thr) != 0ull) T::raise_reference(r, mxl);
+                    if (fresh) {
+                        // Some row that has an allowed key is still without a reference: the largest
+                        // score of its first block with a finite one becomes it.
+                        const float mxl = T::USE_CNEG ? T::max16(r.S) : T::max16(r.S) - r.mref;
+                        if (__builtin_amdgcn_ballot_w64(mxl > r.thr) != 0ull) T::raise_reference(r, mxl);
+                        fresh = __builtin_amdgcn_ballot_w64(live && !(r.thr > -INFINITY)) != 0ull;
+                    }
                     // The LDS requests for M(n) go out between the exponentials, a quarter of them
                     // behind every second pair: K of the next block (the lower half of this tile or
                     // the upper half of the next tile), which M(n) takes first, and V^T of this block.
@@ -648,8 +659,20 @@ void attn_pipe_kernel(Problem pb, CountCfg cc, const h16_t* __restrict__ q, cons
                         }
                         __builtin_amdgcn_sched_barrier(0);
                     };
-                    if constexpr (!T::USE_CNEG) T::template exponentials<true>(r, r.mref, reads);
-                    else T::template exponentials<false>(r, 0.f, reads);
+                    float bsum;
+                    if constexpr (!T::USE_CNEG) bsum = T::template exponentials<true>(r, r.mref, reads);
+                    else bsum = T::template exponentials<false>(r, 0.f, reads);
+                    // The reference follows the scores lazily, and what tells that it has fallen too
+                    // far behind is the sum the phase forms anyway: no row maximum in the common case.
+                    // Then the reference goes up to the row's largest score of this block and the
+                    // exponentials of the block are taken again; O and l do not hold this block yet.
+                    if (__builtin_amdgcn_ballot_w64(bsum > PIPE_SUM_LIMIT) != 0ull) {
+                        const float mxl = T::USE_CNEG ? T::max16(r.S) : T::max16(r.S) - r.mref;
+                        T::raise_reference(r, mxl);
+                        if constexpr (!T::USE_CNEG) bsum = T::template exponentials<true>(r, r.mref, [](int) {});
+                        else bsum = T::template exponentials<false>(r, 0.f, [](int) {});
+                    }
+                    r.l += bsum;
                     // The weights are wanted here: without a use at this point the compiler sinks the
                     // exponentials into the matrix phase, down to the block of their first MFMA.
                     asm volatile("" : "+v"(r.P[0]), "+v"(r.P[1]), "+v"(r.l));
