@@ -162,6 +162,27 @@ attn_status attn_forward(attn_ctx* ctx, const void* X, const void* Wq, const voi
                          const void* Wv, int32_t scheme, void* out, void* hip_stream);
 
 /*
+ * attn_forward on sequences of different lengths stored back to back, without padding (not in
+ * the paper, which has one sequence; batch items are independent, and a vector past an item's
+ * length would be in no allowed pair under Sec. 5.1's rule applied to padding).
+ * row_offsets_dev: device array of batch + 1 int32, non-decreasing, row_offsets_dev[0] = 0: item b
+ * is rows row_offsets_dev[b] .. row_offsets_dev[b + 1] - 1 of X and of out, both
+ * [row_offsets_dev[batch]][...] row-major; its length must not exceed the context's n (a longer
+ * item is cut at n: its later rows take no part and their rows of out are left as they were).
+ * Pair (i, j) of item b needs i, j below the item's length besides the scheme's own rule; only
+ * rows that exist are projected, walked and written, and attn_stats afterwards reports the
+ * counts for these lengths (pairs with both i and j below the length).  The array is read by the
+ * kernels of the call only.  Key lengths set with attn_set_key_lengths are not used by this call.
+ * Only on the matrix-core path (bfloat16, d_k 64 or 128, d_model a multiple of 8, X 16-byte and
+ * out 8-byte aligned) and for ATTN_SCHEME_FULL and ATTN_SCHEME_CAUSAL: anything else returns
+ * UNSUPPORTED, and so does a context created with ATTN_FLAG_NO_SKIP.  ATTN_FLAG_FUSE_Q_PROJECTION
+ * is ignored.  Other errors as for attn_forward.
+ */
+attn_status attn_forward_packed(attn_ctx* ctx, const int32_t* row_offsets_dev, const void* X,
+                                const void* Wq, const void* Wk, const void* Wv, int32_t scheme,
+                                void* out, void* hip_stream);
+
+/*
  * Wait for the stream of the last attn_forward and report its executed-versus-full
  * counts.  The closed-form fields are evaluated on the host with the key lengths that
  * call ran with (they are copied back for that: the array it was given must still be

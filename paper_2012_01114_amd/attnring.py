@@ -23,7 +23,7 @@ ATTN_FLAG_NARROW_TILES = 4
 ATTN_FLAG_SKIP_PADDED_ROWS = 8
 ATTN_FLAG_FUSE_Q_PROJECTION = 16
 
-EXPORTS = ("attn_init", "attn_set_key_lengths", "attn_forward", "attn_forward_static", "attn_stats",
+EXPORTS = ("attn_init", "attn_set_key_lengths", "attn_forward", "attn_forward_packed", "attn_forward_static", "attn_stats",
            "attn_profile", "attn_profile_read", "attn_last_error", "attn_destroy")
 ATTN_STATIC_SCRATCH_MIB = 64
 
@@ -72,6 +72,8 @@ def load():
     lib.attn_set_key_lengths.argtypes = [vp, vp]
     lib.attn_forward.restype = C.c_int
     lib.attn_forward.argtypes = [vp, vp, vp, vp, vp, C.c_int32, vp, vp]
+    lib.attn_forward_packed.restype = C.c_int
+    lib.attn_forward_packed.argtypes = [vp, vp, vp, vp, vp, vp, C.c_int32, vp, vp]
     lib.attn_forward_static.restype = C.c_int
     lib.attn_forward_static.argtypes = [C.POINTER(attn_config), vp, vp, vp, vp, vp, C.c_int32, vp, vp]
     lib.attn_stats.restype = C.c_int
@@ -131,6 +133,17 @@ def attn_forward(ctx, X, Wq, Wk, Wv, scheme: int, out, stream=None) -> None:
         stream = torch.cuda.current_stream(X.device)
     st = load().attn_forward(ctx, _ptr(X), _ptr(Wq), _ptr(Wk), _ptr(Wv), int(scheme), _ptr(out),
                              C.c_void_p(stream.cuda_stream))
+    _check(st, ctx)
+
+
+def attn_forward_packed(ctx, row_offsets_dev, X, Wq, Wk, Wv, scheme: int, out, stream=None) -> None:
+    """attn_forward on items stored back to back: item b is rows row_offsets_dev[b] .. row_offsets_dev[b+1]-1
+    of X and out (row_offsets_dev: int32 GPU tensor of batch + 1 entries)."""
+    import torch
+    if stream is None:
+        stream = torch.cuda.current_stream(X.device)
+    st = load().attn_forward_packed(ctx, _ptr(row_offsets_dev), _ptr(X), _ptr(Wq), _ptr(Wk), _ptr(Wv), int(scheme),
+                                    _ptr(out), C.c_void_p(stream.cuda_stream))
     _check(st, ctx)
 
 

@@ -406,6 +406,10 @@ void attn_pipe_kernel(Problem pb, CountCfg cc, const h16_t* __restrict__ q, cons
     int len = N;
     if (pb.lens) { len = pb.lens[bb]; len = len < 0 ? 0 : (len > N ? N : len); }
     const int rlen = pb.skip_rows ? len : N;  // query rows at or past it take part in no pair
+    // Rows of `out`: n per batch item, or, in the packed layout, the item's own vectors and nothing
+    // after them (the rows that follow belong to the next item and are not to be written).
+    const size_t out_row0 = pb.row0 ? (size_t)pb.row0[bb] : (size_t)bb * N;
+    const int n_out = pb.row0 ? rlen : N;
     const int nkt_all = Npad / BC;
 
     const h16_t* qh = q + (size_t)bh * Npad * DK;
@@ -448,7 +452,7 @@ void attn_pipe_kernel(Problem pb, CountCfg cc, const h16_t* __restrict__ q, cons
                 if (n_live - 1 - x < x || (pass == 1 && x == n_live - 1 - x)) continue;
             } else {
                 I = n_live + (pass - 2) * per_head + x;
-                if (I >= n_qtiles) continue;
+                if (I >= n_qtiles || pb.row0) continue;  // packed layout: no such rows in `out`
                 zeros_only = true;
             }
         } else {
@@ -770,12 +774,12 @@ void attn_pipe_kernel(Problem pb, CountCfg cc, const h16_t* __restrict__ q, cons
                     *(u32x2*)(stage + ln_e * (DK * 2) + ((c ^ (ln_e & (CPR - 1))) << 4) + 8 * g_e) = w;
                 }
             __builtin_amdgcn_s_waitcnt(0xC07F);  // lgkmcnt(0): only this wavefront reads what it wrote
-            bf16_t* obase = out + ((size_t)bb * N + i0w) * ((size_t)pb.H * DK) + (size_t)h * DK;
+            bf16_t* obase = out + (out_row0 + i0w) * ((size_t)pb.H * DK) + (size_t)h * DK;
 #pragma unroll
             for (int it = 0; it < 32 * CPR / 64; ++it) {
                 const int row = it * (64 / CPR) + le / CPR, c = le % CPR;
                 const u32x4 v = *(const u32x4*)(stage + row * (DK * 2) + ((c ^ (row & (CPR - 1))) << 4));
-                if (i0w + row < N) *(u32x4*)(obase + (size_t)row * ((size_t)pb.H * DK) + c * 8) = v;
+                if (i0w + row < n_out) *(u32x4*)(obase + (size_t)row * ((size_t)pb.H * DK) + c * 8) = v;
             }
             if (pass + 1 < n_pass) {
                 // the next pass refills the ring: every wavefront has to be done with its staging first

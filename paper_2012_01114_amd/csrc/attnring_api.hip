@@ -28,6 +28,7 @@ struct attn_ctx {
     float* sym_work;  // q = k = v scheme, matrix-core path: partial row states (allocated on first use)
     unsigned long long* counters;
     const int32_t* lens;
+    int32_t* packed_lens;  // [batch]: the lengths a packed call derives from its row offsets
     // last forward
     const int32_t* last_lens;  // the key lengths that call ran with
     bool last_rows_too;
@@ -73,7 +74,7 @@ attn_status hip_fail(attn_ctx* ctx, const char* what, hipError_t e)
 
 void free_all(attn_ctx* c)
 {
-    void* ptrs[] = {c->qb, c->kb, c->vtb, c->wt, c->qf, c->kf, c->vf, c->scores, c->sym_work, c->counters};
+    void* ptrs[] = {c->qb, c->kb, c->vtb, c->wt, c->qf, c->kf, c->vf, c->scores, c->sym_work, c->counters, c->packed_lens};
     for (void* p : ptrs)
         if (p) (void)hipFree(p);
     for (hipEvent_t e : c->events) (void)hipEventDestroy(e);
@@ -90,6 +91,7 @@ Problem make_problem(const attn_ctx* c, int scheme)
     pb.no_q = scheme == ATTN_SCHEME_SYMMETRIC;
     pb.is_bf16 = c->cfg.dtype == ATTN_BF16;
     pb.lens = c->lens;
+    pb.row0 = nullptr;
     pb.counters = c->counters;
     return pb;
 }
@@ -116,6 +118,16 @@ __global__ __launch_bounds__(1024) void sum_counters_kernel(unsigned long long* 
         for (int i = 0; i < CNT_SLOTS / 64; ++i) v += part[threadIdx.x][i];
         c[CNT_TOTALS + threadIdx.x] = v;
     }
+}
+
+// Packed layout: item b holds rows row0[b] .. row0[b + 1] - 1; its length, kept inside 0 .. n.
+__global__ __launch_bounds__(256) void lens_from_offsets_kernel(const int32_t* __restrict__ row0,
+                                                                int32_t* __restrict__ lens, int B, int N)
+{
+    const int b = blockIdx.x * 256 + threadIdx.x;
+    if (b >= B) return;
+    const int len = row0[b + 1] - row0[b];
+    lens[b] = len < 0 ? 0 : (len > N ? N : len);
 }
 
 attn_status ensure_generic_workspace(attn_ctx* c)
@@ -276,6 +288,7 @@ attn_status attn_init(const attn_config* cfg, attn_ctx** out_ctx)
     c->mfma_shape = matrix_core_shape(cfg);
     e = hipMalloc((void**)&c->counters, sizeof(unsigned long long) * CNT_BUFFER_WORDS);
     if (e == hipSuccess) e = hipMemset(c->counters, 0, sizeof(unsigned long long) * CNT_BUFFER_WORDS);
+    if (e == hipSuccess) e = hipMalloc((void**)&c->packed_lens, sizeof(int32_t) * (size_t)(cfg->batch > 0 ? cfg->batch : 1));
     if (e == hipSuccess && c->mfma_shape) {
         const size_t qkv = (size_t)cfg->batch * c->Npad * hd * sizeof(h16_t);
         h16_t** dst[3] = {&c->qb, &c->kb, &c->vtb};
@@ -312,8 +325,9 @@ attn_status attn_set_key_lengths(attn_ctx* ctx, const int32_t* lens_dev)
     return ATTN_OK;
 }
 
-attn_status attn_forward(attn_ctx* ctx, const void* X, const void* Wq, const void* Wk, const void* Wv,
-                         int32_t scheme, void* out, void* hip_stream)
+// attn_forward (row0 == NULL) and attn_forward_packed (row0: device, the items' first rows)
+static attn_status forward_on(attn_ctx* ctx, const int32_t* row0, const void* X, const void* Wq, const void* Wk,
+                              const void* Wv, int32_t scheme, void* out, void* hip_stream)
 {
     if (!ctx) return fail(nullptr, ATTN_ERR_INVALID, "attn_forward: NULL context%s");
     if (!X || !out) return fail(ctx, ATTN_ERR_INVALID, "attn_forward: X and out must not be NULL%s");
@@ -322,6 +336,7 @@ attn_status attn_forward(attn_ctx* ctx, const void* X, const void* Wq, const voi
     const attn_config& cf = ctx->cfg;
     const int hd = cf.n_heads * cf.d_k;
     if (scheme == ATTN_SCHEME_SYMMETRIC) {
+        if (row0) return fail(ctx, ATTN_ERR_UNSUPPORTED, "attn_forward_packed: the q=k=v scheme takes no lengths%s");
         if (ctx->lens) return fail(ctx, ATTN_ERR_UNSUPPORTED, "attn_forward: key lengths with the q=k=v scheme%s");
         if (!Wq && cf.d_model != hd)
             return fail(ctx, ATTN_ERR_INVALID, "attn_forward: Wq == NULL needs d_model == n_heads*d_k%s");
@@ -331,6 +346,11 @@ attn_status attn_forward(attn_ctx* ctx, const void* X, const void* Wq, const voi
     }
     hipStream_t s = (hipStream_t)hip_stream;
     Problem pb = make_problem(ctx, scheme);
+    if (row0) {  // the items' lengths are their key lengths, and no row past them exists
+        pb.lens = ctx->packed_lens;
+        pb.row0 = row0;
+        pb.skip_rows = true;
+    }
     hipError_t e;
 
     hipEvent_t* ev = nullptr;
@@ -361,6 +381,18 @@ attn_status attn_forward(attn_ctx* ctx, const void* X, const void* Wq, const voi
     const bool sym_fits = sym && Wq != nullptr && sym_pair_workspace_floats(pb) * sizeof(float) <= MAX_SCORE_BYTES;
     const bool use_mfma = ctx->mfma_shape && (!sym || sym_fits) && aligned_to(X, 16) && aligned_to(out, 8) &&
                           aligned_to(Wq, 2) && (sym || (aligned_to(Wk, 2) && aligned_to(Wv, 2)));
+    if (row0 && (cf.flags & ATTN_FLAG_NO_SKIP))
+        return fail(ctx, ATTN_ERR_UNSUPPORTED, "attn_forward_packed: not with ATTN_FLAG_NO_SKIP%s");
+    if (row0 && !use_mfma)
+        return fail(ctx, ATTN_ERR_UNSUPPORTED,
+                    "attn_forward_packed: needs the matrix-core path (bfloat16, d_k 64 or 128, d_model a multiple "
+                    "of 8, X 16-byte and out 8-byte aligned)%s");
+    if (row0) {
+        hipLaunchKernelGGL(lens_from_offsets_kernel, dim3((cf.batch + 255) / 256), dim3(256), 0, s, row0,
+                           ctx->packed_lens, cf.batch, cf.n);
+        e = hipGetLastError();
+        CHECK("launch lens_from_offsets");
+    }
     if (sym && use_mfma) { Wk = Wq; Wv = Wq; }  // one set of vectors in all three roles (Sec. 4.1)
     if (sym && use_mfma && !ctx->sym_work) {
         e = hipMalloc((void**)&ctx->sym_work, sym_pair_workspace_floats(pb) * sizeof(float));
@@ -381,7 +413,7 @@ attn_status attn_forward(attn_ctx* ctx, const void* X, const void* Wq, const voi
             prepared = true;
         }
         // queries projected inside the attention kernel: when asked for and the weights are read in place
-        const bool fuse_q = !sym && (cf.flags & ATTN_FLAG_FUSE_Q_PROJECTION) != 0 &&
+        const bool fuse_q = !sym && !row0 && (cf.flags & ATTN_FLAG_FUSE_Q_PROJECTION) != 0 &&
                             proj_reads_weights_in_place(pb, (const bf16_t*)Wq, (const bf16_t*)Wk, (const bf16_t*)Wv);
         if (fuse_q) pb.no_q = true;
         e = launch_proj_mfma(pb, (const bf16_t*)X, (const bf16_t*)Wq, (const bf16_t*)Wk, (const bf16_t*)Wv, ctx->wt,
@@ -444,11 +476,25 @@ attn_status attn_forward(attn_ctx* ctx, const void* X, const void* Wq, const voi
         ctx->prof_calls += 1;
     }
     ctx->last_stream = s;
-    ctx->last_lens = ctx->lens;
+    ctx->last_lens = pb.lens;
     ctx->last_rows_too = pb.skip_rows;
     ctx->last_scheme = scheme;
     ctx->have_forward = true;
     return ATTN_OK;
+}
+
+attn_status attn_forward(attn_ctx* ctx, const void* X, const void* Wq, const void* Wk, const void* Wv,
+                         int32_t scheme, void* out, void* hip_stream)
+{
+    return forward_on(ctx, nullptr, X, Wq, Wk, Wv, scheme, out, hip_stream);
+}
+
+attn_status attn_forward_packed(attn_ctx* ctx, const int32_t* row_offsets_dev, const void* X, const void* Wq,
+                                const void* Wk, const void* Wv, int32_t scheme, void* out, void* hip_stream)
+{
+    if (!ctx) return fail(nullptr, ATTN_ERR_INVALID, "attn_forward_packed: NULL context%s");
+    if (!row_offsets_dev) return fail(ctx, ATTN_ERR_INVALID, "attn_forward_packed: NULL row offsets%s");
+    return forward_on(ctx, row_offsets_dev, X, Wq, Wk, Wv, scheme, out, hip_stream);
 }
 
 attn_status attn_forward_static(const attn_config* cfg, const int32_t* lens_dev, const void* X, const void* Wq,
@@ -473,6 +519,7 @@ attn_status attn_forward_static(const attn_config* cfg, const int32_t* lens_dev,
     pb.no_q = false;
     pb.is_bf16 = true;
     pb.lens = lens_dev;
+    pb.row0 = nullptr;
     if (!matrix_core_shape(cfg) || !aligned_to(X, 16) || !aligned_to(out, 8) ||
         !proj_reads_weights_in_place(pb, (const bf16_t*)Wq, (const bf16_t*)Wk, (const bf16_t*)Wv))
         return fail(nullptr, ATTN_ERR_UNSUPPORTED,

@@ -24,6 +24,7 @@ struct Problem {
     bool no_q;           // the projection kernel leaves q out (q = k = v scheme; queries projected by the attention kernel)
     bool is_bf16;        // storage type of X, W, out
     const int* lens;     // device, [B] or nullptr
+    const int* row0;     // packed layout of x and out: device, [B + 1] first rows of the batch items; else nullptr
     unsigned long long* counters;  // device: CNT_SLOTS slots of (logical tiles, physical score blocks), then totals
 };
 
@@ -40,6 +41,20 @@ __device__ __forceinline__ void count_add(unsigned long long* counters, unsigned
     unsigned long long* slot = counters + (size_t)(item & (CNT_SLOTS - 1)) * CNT_SLOT_WORDS;
     if (logical) atomicAdd(&slot[CNT_LOGICAL], logical);
     if (phys) atomicAdd(&slot[CNT_PHYS], phys);
+}
+
+// Row of the caller's x (and out) that holds vector i of batch item bb.  Padded layout: every item
+// has N rows.  Packed layout: item bb has rows row0[bb] .. row0[bb + 1] - 1 and nothing follows its
+// last vector; a vector at or past its length is in no allowed pair, and a read for it (whole tiles
+// are fetched) is pointed at a row that exists.
+__device__ __forceinline__ unsigned source_row(const int* __restrict__ row0, int Bsz, int N, int bb, int i)
+{
+    if (row0 == nullptr) return (unsigned)(bb * N + (i < N ? i : N - 1));
+    const int first = row0[bb], len = row0[bb + 1] - first, total = row0[Bsz];
+    i = i < len ? i : len - 1;
+    int r = first + (i < 0 ? 0 : i);
+    r = r < total ? r : total - 1;
+    return (unsigned)(r < 0 ? 0 : r);
 }
 
 // ---- generic float-compute path (any shape, f32 or bf16 storage) ----------

@@ -153,7 +153,8 @@ __global__ __launch_bounds__(256) void proj_mfma_kernel(int Bsz, int N, int Npad
                                                         const bf16_t* __restrict__ X,
                                                         const bf16_t* __restrict__ Wt, h16_t* __restrict__ qo,
                                                         h16_t* __restrict__ ko, h16_t* __restrict__ vto,
-                                                        int tiles_x, int tiles_w, float qscale, const int* __restrict__ lens, bool skip_q_rows, bool no_q)
+                                                        int tiles_x, int tiles_w, float qscale, const int* __restrict__ lens, bool skip_q_rows, bool no_q,
+                                                        const int* __restrict__ row0)
 {
     constexpr int WT = BT / 2;          // wavefront tile edge
     constexpr int NB = WT / 32;         // MFMA blocks per edge
@@ -190,9 +191,7 @@ __global__ __launch_bounds__(256) void proj_mfma_kernel(int Bsz, int N, int Npad
         const int row = (tid >> 3) + 32 * u;
         const int xr = x0 + row;
         const int bb = xr / Npad;
-        int i = xr - bb * Npad;
-        i = i < N ? i : N - 1;
-        xoff[u] = (unsigned)(bb * N + i) * (unsigned)D;
+        xoff[u] = source_row(row0, Bsz, N, bb, xr - bb * Npad) * (unsigned)D;
         woff[u] = (unsigned)(w0 + row) * (unsigned)D;
     }
 
@@ -327,7 +326,7 @@ void proj_dma_kernel(int Bsz, int N, int Npad, int D, int H, int d, const bf16_t
                      const bf16_t* __restrict__ Wq, const bf16_t* __restrict__ Wk, const bf16_t* __restrict__ Wv,
                      h16_t* __restrict__ qo, h16_t* __restrict__ ko, h16_t* __restrict__ vto, int tiles_x,
                      int tiles_w, float qscale, const int* __restrict__ lens, bool skip_q_rows, bool no_q,
-                     unsigned long long* __restrict__ counters)
+                     const int* __restrict__ row0, unsigned long long* __restrict__ counters)
 {
     constexpr int NW = WR * WC;
     constexpr int TA = BT / WR, TB = BT / WC;    // wavefront tile: TA rows of the A side, TB of the B side
@@ -387,9 +386,7 @@ void proj_dma_kernel(int Bsz, int N, int Npad, int D, int H, int d, const bf16_t
         const int c = (lane & 7) ^ ((row >> 1) & 7);
         const int xr = x0 + row;
         const int bb = xr / Npad;
-        int i = xr - bb * Npad;
-        i = i < N ? i : N - 1;
-        xoff[u] = 2u * ((unsigned)(bb * N + i) * (unsigned)D + c * 8);
+        xoff[u] = 2u * (source_row(row0, Bsz, N, bb, xr - bb * Npad) * (unsigned)D + c * 8);
     }
 #pragma unroll
     for (int u = 0; u < WPW; ++u) {
@@ -701,7 +698,7 @@ hipError_t launch_dma(const Problem& pb, const bf16_t* X, const bf16_t* Wq, cons
     const int grid = ((tiles_x * tiles_w + 7) / 8) * 8;
     hipLaunchKernelGGL((proj_dma_kernel<BT, WR, WC>), dim3(grid), dim3(64 * WR * WC), 0, s, pb.B, pb.N, pb.Npad, pb.D,
                        pb.H, pb.d, X, Wq, Wk, Wv, q, k, vt, tiles_x, tiles_w, qscale, pb.noskip ? nullptr : pb.lens,
-                       pb.skip_rows, pb.no_q, pb.counters);
+                       pb.skip_rows, pb.no_q, pb.row0, pb.counters);
     return hipGetLastError();
 }
 
@@ -714,7 +711,7 @@ hipError_t launch_bt(const Problem& pb, const bf16_t* X, const bf16_t* Wt, h16_t
     const int tiles_w = 3 * pb.H * pb.d / BT;
     const int grid = ((tiles_x * tiles_w + 7) / 8) * 8;
     hipLaunchKernelGGL(proj_mfma_kernel<BT>, dim3(grid), dim3(256), 0, s, pb.B, pb.N, pb.Npad, pb.D, pb.H, pb.d, X, Wt,
-                       q, k, vt, tiles_x, tiles_w, qscale, pb.noskip ? nullptr : pb.lens, pb.skip_rows, pb.no_q);
+                       q, k, vt, tiles_x, tiles_w, qscale, pb.noskip ? nullptr : pb.lens, pb.skip_rows, pb.no_q, pb.row0);
     return hipGetLastError();
 }
 

@@ -103,6 +103,30 @@ class GpuRun:
         stats = ar.attn_stats(self.ctx)          # waits for the stream
         return self.out.to("cpu").to(self.torch.float64).numpy(), stats
 
+    def forward_packed(self, scheme, lens, guard_rows=8):
+        """The items cut to `lens` and stored back to back; returns the output laid out as
+        [batch][n][...] again (zeros past the lengths) and the counts.  Rows of `out` past the
+        last item must come back untouched."""
+        torch = self.torch
+        lens = [int(L) for L in lens]
+        offs = np.concatenate([[0], np.cumsum(lens)]).astype(np.int32)
+        total = int(offs[-1])
+        parts = [self.X[b, :L] for b, L in enumerate(lens)]
+        Xp = torch.cat(parts, 0).contiguous() if total else self.X[0, :0].contiguous()
+        if total == 0:  # an allocation to point at
+            Xp = torch.zeros((1, self.w.d_model), dtype=self.X.dtype, device=self.X.device)
+        outp = torch.full((total + guard_rows, self.w.hd), float("nan"), dtype=self.X.dtype, device=self.X.device)
+        offs_dev = torch.from_numpy(offs).to(self.X.device)
+        ar.attn_forward_packed(self.ctx, offs_dev, Xp, self.W[0], self.W[1], self.W[2], scheme, outp)
+        stats = ar.attn_stats(self.ctx)
+        host = outp.to("cpu").to(torch.float64).numpy()
+        assert np.all(np.isnan(host[total:])), "rows past the last item were written"
+        assert not np.any(np.isnan(host[:total])), "a row of an item was left unwritten"
+        full = np.zeros((self.w.batch, self.w.n, self.w.hd))
+        for b, L in enumerate(lens):
+            full[b, :L] = host[offs[b]:offs[b] + L]
+        return full, stats
+
     def close(self):
         if self.ctx is not None:
             self.torch.cuda.synchronize()

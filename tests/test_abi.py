@@ -69,6 +69,7 @@ def test_null_arguments():
     assert lib.attn_profile(None, 1) == ar.ATTN_ERR_INVALID
     assert lib.attn_profile_read(None, None) == ar.ATTN_ERR_INVALID
     assert lib.attn_set_key_lengths(None, None) == ar.ATTN_ERR_INVALID
+    assert lib.attn_forward_packed(None, None, None, None, None, None, 0, None, None) == ar.ATTN_ERR_INVALID
     assert lib.attn_forward_static(None, None, None, None, None, None, 0, None, None) == ar.ATTN_ERR_INVALID
     lib.attn_destroy(None)
     assert isinstance(ar.attn_last_error(None), str)

@@ -294,6 +294,76 @@ def test_padded_rows_left_out(case, scheme):
         assert np.array_equal(outs[0], outs[1])
 
 
+@pytest.mark.parametrize("case", [
+    ("bf16", 3, 320, 64, 2, 64, 40, 0),
+    ("bf16", 3, 704, 128, 2, 64, 88, ar.ATTN_FLAG_WIDE_TILES),
+    ("bf16", 3, 600, 192, 1, 128, 75, 0),
+    ("bf16", 3, 320, 72, 2, 64, 40, 0),      # d_model not in whole 64-deep slices: the other projection kernel
+])
+@pytest.mark.parametrize("scheme", [FULL, CAUSAL])
+def test_packed_layout(case, scheme):
+    """Items stored back to back: the checker's answer for the cut items, and bit for bit what the
+    padded layout gives with the same lengths and the padded rows left out."""
+    dtype, B, n, D, H, d, p, tiles = case
+    w = hp.custom_workload("packed", B, n, D, H, d, p, dtype, scheme, 700 + n)
+    stored, f64 = inputs.make_inputs(w)
+    for lens in (np.array([n // 3 + 1, n, 0], dtype=np.int32), np.array([33, 1, n - 1], dtype=np.int32),
+                 np.array([0, 0, 0], dtype=np.int32)):
+        print(f"[lens] {lens.tolist()}", flush=True)
+        stored["lens"] = lens
+        run = hp.GpuRun(w, stored, flags=tiles | ar.ATTN_FLAG_SKIP_PADDED_ROWS)
+        try:
+            padded, stats_padded = run.forward(scheme)
+            got, stats = run.forward_packed(scheme, lens)
+            again, _ = run.forward_packed(scheme, lens)   # the workspace keeps nothing that matters
+        finally:
+            run.close()
+        worst = hp.tol_check(got, hp.oracle_forward(w, f64, scheme, 0.0, lens=lens, skip_padded_rows=True), w.dtype)
+        hp.report_max_err(f"packed {case[:7]} scheme {scheme} lens {lens.tolist()}", worst, w.dtype)
+        hp.check_counts(stats, hp.oracle_counts(w, scheme, lens, skip_padded_rows=True))
+        assert stats["phys_tiles_executed"] == stats_padded["phys_tiles_executed"]
+        assert np.array_equal(got, padded)
+        assert np.array_equal(got, again)
+
+
+def test_packed_layout_is_refused_off_the_matrix_core_path():
+    w = hp.custom_workload("packed_f32", 2, 64, 64, 1, 64, 4, "f32", CAUSAL, 3)
+    stored, _ = inputs.make_inputs(w)
+    run = hp.GpuRun(w, stored)
+    try:
+        with pytest.raises(ar.AttnError) as e:
+            run.forward_packed(CAUSAL, [10, 20])
+        assert e.value.status == ar.ATTN_ERR_UNSUPPORTED
+    finally:
+        run.close()
+    w = hp.custom_workload("packed_sym", 2, 128, 64, 1, 64, 4, "bf16", SYM, 3)
+    stored, _ = inputs.make_inputs(w)
+    run = hp.GpuRun(w, stored)
+    try:
+        with pytest.raises(ar.AttnError) as e:
+            run.forward_packed(SYM, [10, 20])
+        assert e.value.status == ar.ATTN_ERR_UNSUPPORTED
+    finally:
+        run.close()
+
+
+def test_padded_workload_packed():
+    """The padded workload stored back to back: bit for bit the padded layout's rows below the lengths."""
+    w = inputs.WORKLOADS["padded"]
+    lens = inputs.draw_lengths(w)
+    stored, _ = inputs.make_inputs(w)
+    stored["lens"] = lens
+    run = hp.GpuRun(w, stored, flags=ar.ATTN_FLAG_SKIP_PADDED_ROWS)
+    try:
+        padded, stats_padded = run.forward(w.scheme)
+        got, stats = run.forward_packed(w.scheme, lens)
+    finally:
+        run.close()
+    assert np.array_equal(got, padded)
+    for key in ("pairs_needed", "tiles_executed", "pairs_executed", "phys_tiles_executed"):
+        assert stats[key] == stats_padded[key]
+
+
 def test_padded_workload_with_padded_rows_left_out():
     w = inputs.WORKLOADS["padded"]
     lens = inputs.draw_lengths(w)
