@@ -99,9 +99,10 @@ def cpu_baseline(w, f64, lens, budget_s=12.0, max_heads=256, rows_too=False):
 class Session:
     """One workload resident on the GPU: inputs, context, output buffer."""
 
-    def __init__(self, name, tiles="auto", skip_padded_rows=False, scheme=None, one_weight=False):
+    def __init__(self, name, tiles="auto", skip_padded_rows=False, scheme=None, one_weight=False, packed=False):
         """scheme: run the workload's shape under another scheme; one_weight: Wq in all three roles
-        (the setting in which the q = k = v scheme and the original definition give the same result)."""
+        (the setting in which the q = k = v scheme and the original definition give the same result);
+        packed: the items cut to their lengths and stored back to back (attn_forward_packed)."""
         import torch
         from paper_2012_01114_amd import attnring as ar
         from paper_2012_01114_amd import inputs
@@ -119,14 +120,25 @@ class Session:
         self.out = torch.empty(w.batch, w.n, w.hd, dtype=self.X.dtype, device=dev)
         dt = ar.ATTN_F32 if w.dtype == "f32" else ar.ATTN_BF16
         flags = {"auto": 0, "wide": ar.ATTN_FLAG_WIDE_TILES, "narrow": ar.ATTN_FLAG_NARROW_TILES}[tiles]
-        self.rows_too = skip_padded_rows and self.lens is not None
+        self.packed = packed and self.lens is not None
+        self.rows_too = (skip_padded_rows or self.packed) and self.lens is not None
         if self.rows_too:
             flags |= ar.ATTN_FLAG_SKIP_PADDED_ROWS
+        if self.packed:
+            import numpy as np
+            offs = np.concatenate([[0], np.cumsum(self.lens)]).astype(np.int32)
+            self.offs_dev = torch.from_numpy(offs).to(dev)
+            self.X = torch.cat([self.X[b, :int(L)] for b, L in enumerate(self.lens)], 0).contiguous()
+            self.out = torch.empty(int(offs[-1]), w.hd, dtype=self.X.dtype, device=dev)
         self.ctx = ar.attn_init(w.batch, w.n, w.d_model, w.n_heads, w.d_k, w.p, dt, 0.0, flags)
         ar.attn_set_key_lengths(self.ctx, self.lens_dev)
         self.stream = torch.cuda.current_stream(dev)
 
     def step(self):
+        if self.packed:
+            self.ar.attn_forward_packed(self.ctx, self.offs_dev, self.X, self.Wq, self.Wk, self.Wv, self.w.scheme,
+                                        self.out, self.stream)
+            return
         self.ar.attn_forward(self.ctx, self.X, self.Wq, self.Wk, self.Wv, self.w.scheme, self.out, self.stream)
 
     def flops(self):
@@ -270,15 +282,21 @@ def main():
 
     # the other workloads of the metric: GPU only, same protocol, inputs drawn once each
     others = {}
+    runs = []
     for name in [n for n in args.others.split(",") if n and n != args.workload]:
-        o = Session(name)
+        runs.append((name, {}))
+        if inputs.WORKLOADS[name].padded:  # the same items without their padded rows, in both layouts
+            runs.append((name + "_rows_left_out", {"skip_padded_rows": True}))
+            runs.append((name + "_packed", {"packed": True}))
+    for label, kw in runs:
+        o = Session(label.split("_")[0], **kw)
         o_ms, o_regions, o_prof, o_stats = o.measure(args.steps, args.warmup, args.repeats)
         o_attn, o_proj, o_pairs = o.flops()
         assert o_pairs == o_stats["pairs_needed"][0]
         rec = rates(o_attn, o_proj, o_ms, o_prof)
         rec["ms_per_step"] = round(o_ms, 4)
-        rec["workload"] = describe(o.w, o.lens, False)
-        others[name] = rec
+        rec["workload"] = describe(o.w, o.lens, o.rows_too) + (", stored back to back" if o.packed else "")
+        others[label] = rec
         o.close()
         del o
         torch.cuda.empty_cache()
