@@ -326,6 +326,33 @@ def test_packed_layout(case, scheme):
         assert np.array_equal(got, again)
 
 
+def test_packed_item_longer_than_n_is_cut():
+    """An item with more rows than the context's n: its first n rows are the item, the rest take no part and
+    their rows of out stay as they were."""
+    import torch
+    B, n, D, H, d, p = 2, 128, 64, 2, 64, 16
+    w = hp.custom_workload("packed_cut", B, n, D, H, d, p, "bf16", CAUSAL, 911)
+    stored, f64 = inputs.make_inputs(w)
+    extra = 72                                   # item 0 has n + extra rows, item 1 has 64
+    run = hp.GpuRun(w, stored)
+    try:
+        tail = (torch.randn(extra, D, device=run.X.device) * 3.0).to(run.X.dtype)
+        Xp = torch.cat([run.X[0], tail, run.X[1, :64]], 0).contiguous()
+        offs = torch.tensor([0, n + extra, n + extra + 64], dtype=torch.int32, device=run.X.device)
+        outp = torch.full((Xp.shape[0] + 4, w.hd), float("nan"), dtype=run.X.dtype, device=run.X.device)
+        ar.attn_forward_packed(run.ctx, offs, Xp, run.W[0], run.W[1], run.W[2], CAUSAL, outp)
+        stats = ar.attn_stats(run.ctx)
+        host = outp.to("cpu").to(torch.float64).numpy()
+    finally:
+        run.close()
+    lens = np.array([n, 64], dtype=np.int32)
+    ref = hp.oracle_forward(w, f64, CAUSAL, 0.0, lens=lens, skip_padded_rows=True)
+    hp.tol_check(host[:n], ref[0], w.dtype)
+    hp.tol_check(host[n + extra:n + extra + 64], ref[1, :64], w.dtype)
+    assert np.all(np.isnan(host[n:n + extra])) and np.all(np.isnan(host[n + extra + 64:]))
+    hp.check_counts(stats, hp.oracle_counts(w, CAUSAL, lens, skip_padded_rows=True))
+
+
 def test_packed_layout_is_refused_off_the_matrix_core_path():
     w = hp.custom_workload("packed_f32", 2, 64, 64, 1, 64, 4, "f32", CAUSAL, 3)
     stored, _ = inputs.make_inputs(w)
