@@ -93,3 +93,12 @@ def test_static_entry_point_rejects_before_touching_the_device():
     assert call(n=18, p=4) == ar.ATTN_ERR_SHAPE
     assert call(batch=64, n=8192, n_heads=16) == ar.ATTN_ERR_UNSUPPORTED      # 3 x 1 GiB of q, k, v
     assert "bytes of workspace" in ar.attn_last_error(None)
+
+
+def test_bench_refuses_more_than_one_gpu():
+    """One GPU only: no collectives, no sharding in this library."""
+    import subprocess
+    import sys
+    r = subprocess.run([sys.executable, os.path.join(ROOT, "bench.py"), "--gpus", "2"], capture_output=True, text=True)
+    assert r.returncode != 0
+    assert "one GPU" in (r.stderr + r.stdout)
