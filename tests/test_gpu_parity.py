@@ -294,6 +294,26 @@ def test_padded_rows_left_out(case, scheme):
         assert np.array_equal(outs[0], outs[1])
 
 
+@pytest.mark.parametrize("scheme", [FULL, CAUSAL])
+@pytest.mark.parametrize("flags", [0, ar.ATTN_FLAG_SKIP_PADDED_ROWS])
+def test_key_lengths_with_heads_dealt_over_the_xcds(scheme, flags):
+    """A multiple of eight heads in all and key lengths: every XCD takes every eighth head."""
+    w = hp.custom_workload("dealt", 4, 384, 64, 4, 64, 48, "bf16", scheme, 8181)
+    stored, f64 = inputs.make_inputs(w)
+    lens = np.array([384, 65, 200, 1], dtype=np.int32)
+    stored["lens"] = lens
+    run = hp.GpuRun(w, stored, flags=flags)
+    try:
+        got, stats = run.forward(scheme)
+    finally:
+        run.close()
+    rows_too = bool(flags)
+    worst = hp.tol_check(got, hp.oracle_forward(w, f64, scheme, 0.0, lens=lens, skip_padded_rows=rows_too), w.dtype)
+    hp.report_max_err(f"dealt scheme={scheme} flags={flags}", worst, w.dtype)
+    hp.check_counts(stats, hp.oracle_counts(w, scheme, lens, skip_padded_rows=rows_too))
+    assert stats["phys_tiles_executed"] == hp.expected_phys_blocks(w, scheme, lens, skip_padded_rows=rows_too)
+
+
 @pytest.mark.parametrize("case", [
     ("bf16", 3, 320, 64, 2, 64, 40, 0),
     ("bf16", 3, 704, 128, 2, 64, 88, ar.ATTN_FLAG_WIDE_TILES),
