@@ -33,10 +33,10 @@ MFMA_BF16_PEAK_TFLOPS = 2500.0   # MI355X dense bf16, published
 # HBM/fabric bytes per launch from rocprofv3 counter runs (FETCH_SIZE + WRITE_SIZE, each scaled by what
 # the same counter reads for a plain 1 GiB device copy: x2.00 and x1.00; see profiles/).  They hold for
 # the kernel sources with the hash below; with other sources the bench line carries null.
-TRAFFIC_SOURCES_SHA256 = "5354aee3df147f2fbf8a4c63d8d8137ffc7b314727ac8ff132230551d2f231a1"
+TRAFFIC_SOURCES_SHA256 = "d6d84a6e2c23402829acc8b19ff0c46099659cc391b4ec8a6d7f0a3061044e99"
 TRAFFIC_BYTES = {
-    "long": {"projection": int((2 * 589960 + 196640) * 1024), "attention": int((2 * 143040 + 65792) * 1024)},
-    "causal": {"projection": int((2 * 38899 + 36896) * 1024), "attention": int((2 * 18643 + 12480) * 1024)},
+    "long": {"projection": int((2 * 589960 + 196640) * 1024), "attention": int((2 * 151010 + 65792) * 1024)},
+    "causal": {"projection": int((2 * 39037 + 36896) * 1024), "attention": int((2 * 18670 + 12480) * 1024)},
 }
 
 
