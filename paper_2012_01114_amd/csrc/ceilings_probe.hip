@@ -137,7 +137,139 @@ int run(int waves_per_simd, int iters, int random_operands, double* ns_per_group
     return rc;
 }
 
+// The instruction stream of one 32 x 32 block of the attention walk at d_k = 64, without any memory
+// behind it (no copies into LDS, no barrier): a vector phase (16 exponentials per lane, their packing
+// and their row sums, the check of the block sum) and a matrix phase (the 4-MFMA score chain of the
+// next block, whose accumulator starts at minus the reference, and the 4 weighted-sum MFMAs), in
+// the order of the kernel (DEFERRED 0) or with the weighted sum of the block before issued between
+// the exponentials (DEFERRED 1); READS adds the 8 LDS fragment reads of a block.  Operands random.
+template <int DEFERRED, int READS>
+__global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(3, 3)))
+void block_kernel(float* out, long long* cycles, int iters, float seed)
+{
+    __shared__ __attribute__((aligned(16))) unsigned char lds[32768];
+    unsigned h = threadIdx.x * 2654435761u + blockIdx.x * 40503u;
+    for (int i = threadIdx.x; i < 32768 / 4; i += blockDim.x) ((unsigned*)lds)[i] = hashed_half2(h);
+    __syncthreads();
+    u32x4 qf[4], kf[4], vf[4];
+    for (int j = 0; j < 4; ++j)
+        for (int c = 0; c < 4; ++c) { qf[j][c] = hashed_half2(h); kf[j][c] = hashed_half2(h); vf[j][c] = hashed_half2(h); }
+    f32x16 O[2], S, Cneg;
+    for (int e = 0; e < 16; ++e) { O[0][e] = O[1][e] = 0.f; S[e] = seed * e; Cneg[e] = -seed; }
+    u32x4 P[2][2];
+    for (int a = 0; a < 2; ++a)
+        for (int b = 0; b < 2; ++b) P[a][b] = u32x4{0u, 0u, 0u, 0u};
+    float l = 0.f;
+    const unsigned char* lane_lds = lds + (threadIdx.x & 63) * 16 + (threadIdx.x >> 6) * 8192;
+    auto mf = [](u32x4 a, u32x4 b, f32x16 c) {
+        return __builtin_amdgcn_mfma_f32_32x32x16_f16(__builtin_bit_cast(f16x8, a), __builtin_bit_cast(f16x8, b), c, 0, 0, 0);
+    };
+    const long long t0 = __builtin_readcyclecounter();
+#pragma nounroll
+    for (int it = 0; it < iters; ++it) {
+#pragma unroll
+        for (int half = 0; half < 2; ++half) {
+            const int set = DEFERRED ? half : 0, prev = DEFERRED ? 1 - half : 0;
+            float ps0 = 0.f, ps1 = 0.f;
+#pragma unroll
+            for (int p = 0; p < 8; ++p) {
+                if (DEFERRED && (p & 1) == 0) {
+                    __builtin_amdgcn_sched_barrier(0);
+                    const int e = p >> 1;
+                    O[e & 1] = mf(vf[e], P[prev][e >> 1], O[e & 1]);
+                    __builtin_amdgcn_sched_barrier(0);
+                }
+                const float p0 = __builtin_amdgcn_exp2f(S[2 * p] * 1e-3f), p1 = __builtin_amdgcn_exp2f(S[2 * p + 1] * 1e-3f);
+                P[set][p >> 2][p & 3] = pack_f16(p0, p1);
+                ps0 += p0;
+                ps1 += p1;
+                if (READS && (p & 1)) {
+                    __builtin_amdgcn_sched_barrier(0);
+                    const int q = p >> 1;
+                    kf[q] = *(const u32x4*)(lane_lds + q * 1024);
+                    vf[q] = *(const u32x4*)(lane_lds + 4096 + q * 1024);
+                    __builtin_amdgcn_sched_barrier(0);
+                }
+            }
+            const float bs = ps0 + ps1;
+            if (__builtin_amdgcn_ballot_w64(bs > 1e30f) != 0ull) {
+                for (int e = 0; e < 16; ++e) { O[0][e] *= 0.5f; O[1][e] *= 0.5f; }
+            }
+            l += bs;
+            asm volatile("" : "+v"(P[set][0]), "+v"(P[set][1]), "+v"(l));
+            __builtin_amdgcn_sched_barrier(0);
+            __builtin_amdgcn_s_setprio(1);
+            asm volatile("v_mfma_f32_32x32x16_f16 %0, %1, %2, %3" : "=&v"(S) : "v"(kf[0]), "v"(qf[0]), "v"(Cneg));
+            for (int ks = 1; ks < 4; ++ks) S = mf(kf[ks], qf[ks], S);
+            if (!DEFERRED)
+                for (int e = 0; e < 4; ++e) O[e & 1] = mf(vf[e], P[0][e >> 1], O[e & 1]);
+            __builtin_amdgcn_s_setprio(0);
+        }
+    }
+    const long long t1 = __builtin_readcyclecounter();
+    float r = l;
+    for (int e = 0; e < 16; ++e) r += O[0][e] + O[1][e] + S[e];
+    out[blockIdx.x * blockDim.x + threadIdx.x] = r;
+    if (threadIdx.x == 0) cycles[blockIdx.x] = t1 - t0;
+}
+
+template <int DEFERRED, int READS>
+int run_block(int waves_per_simd, int iters, double* ns_per_block, double* cycles_per_block)
+{
+    int dev = 0, cus = 0;
+    if (hipGetDevice(&dev) != hipSuccess) return 5;
+    if (hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess) return 5;
+    const int nblk = cus * waves_per_simd;
+    float* out = nullptr;
+    long long* cyc = nullptr;
+    if (hipMalloc((void**)&out, sizeof(float) * nblk * 256) != hipSuccess) return 4;
+    if (hipMalloc((void**)&cyc, sizeof(long long) * nblk) != hipSuccess) { (void)hipFree(out); return 4; }
+    hipEvent_t e0, e1;
+    int rc = 0;
+    if (hipEventCreate(&e0) != hipSuccess || hipEventCreate(&e1) != hipSuccess) rc = 5;
+    if (!rc) {
+        hipLaunchKernelGGL((block_kernel<DEFERRED, READS>), dim3(nblk), dim3(256), 0, 0, out, cyc, 10, 0.01f);
+        (void)hipEventRecord(e0, 0);
+        hipLaunchKernelGGL((block_kernel<DEFERRED, READS>), dim3(nblk), dim3(256), 0, 0, out, cyc, iters, 0.01f);
+        (void)hipEventRecord(e1, 0);
+        if (hipDeviceSynchronize() != hipSuccess) rc = 5;
+    }
+    if (!rc) {
+        float ms = 0.f;
+        (void)hipEventElapsedTime(&ms, e0, e1);
+        long long* hcyc = new long long[nblk];
+        (void)hipMemcpy(hcyc, cyc, sizeof(long long) * nblk, hipMemcpyDeviceToHost);
+        double avg = 0;
+        for (int i = 0; i < nblk; ++i) avg += (double)hcyc[i];
+        delete[] hcyc;
+        // per SIMD: its wavefronts each do 2 * iters blocks in the measured time
+        *ns_per_block = (double)ms * 1e6 / (2.0 * iters) / waves_per_simd;
+        *cycles_per_block = avg / nblk / (2.0 * iters);   // of one wavefront
+    }
+    (void)hipEventDestroy(e0);
+    (void)hipEventDestroy(e1);
+    (void)hipFree(out);
+    (void)hipFree(cyc);
+    return rc;
+}
+
 }  // namespace
+
+// One block of the d_k = 64 walk as a wavefront issues it, nothing behind it: deferred 0 / 1 (see
+// block_kernel), lds_reads 0 / 1, waves_per_simd 1..3.  Results: nanoseconds per block and SIMD,
+// shader cycles per block of one wavefront.  Returns as attn_probe_run.
+extern "C" int attn_probe_block(int deferred, int lds_reads, int waves_per_simd, int iters, double* ns_per_block,
+                                double* cycles_per_block)
+{
+    if (deferred < 0 || deferred > 1 || lds_reads < 0 || lds_reads > 1 || waves_per_simd < 1 || waves_per_simd > 3 ||
+        iters < 1 || !ns_per_block || !cycles_per_block)
+        return 1;
+    if (deferred)
+        return lds_reads ? run_block<1, 1>(waves_per_simd, iters, ns_per_block, cycles_per_block)
+                         : run_block<1, 0>(waves_per_simd, iters, ns_per_block, cycles_per_block);
+    return lds_reads ? run_block<0, 1>(waves_per_simd, iters, ns_per_block, cycles_per_block)
+                     : run_block<0, 0>(waves_per_simd, iters, ns_per_block, cycles_per_block);
+}
 
 // units: bit 0 MFMAs, bit 1 softmax vector work, bit 2 LDS fragment reads; density: 1 = 8 pairs per
 // group (d_k = 128), 2 = 16 pairs (d_k = 64); waves_per_simd 1..3.  Results per 16-MFMA group and

@@ -27,6 +27,19 @@ def run(units: int, density: int, waves_per_simd: int, random_operands: bool, it
     return ns.value, cyc.value
 
 
+def run_block(deferred: bool, lds_reads: bool, waves_per_simd: int, iters: int = 4000):
+    """One block of the d_k = 64 walk as the kernel issues it (vector phase, then matrix phase), with
+    nothing behind it; deferred: the weighted sum of the block before between the exponentials."""
+    lib = C.CDLL(LIB_PATH)
+    lib.attn_probe_block.restype = C.c_int
+    lib.attn_probe_block.argtypes = [C.c_int] * 4 + [C.POINTER(C.c_double)] * 2
+    ns, cyc = C.c_double(), C.c_double()
+    rc = lib.attn_probe_block(1 if deferred else 0, 1 if lds_reads else 0, waves_per_simd, iters, C.byref(ns), C.byref(cyc))
+    if rc:
+        raise RuntimeError(f"attn_probe_block returned {rc}")
+    return ns.value, cyc.value
+
+
 def main():
     rows = []
     for density in (1, 2):
@@ -42,6 +55,16 @@ def main():
                         rec["mfma_tflops_chip"] = round(MFMA_FLOP_PER_GROUP * N_SIMD / ns / 1e3, 1)
                     rows.append(rec)
                     print(json.dumps(rec), flush=True)
+    for waves in (1, 2, 3):
+        for deferred in (False, True):
+            for reads in (False, True):
+                ns, cyc = run_block(deferred, reads, waves)
+                rec = {"block_of_the_walk": "d_k 64", "weighted_sum": "one block late, between the exponentials" if deferred
+                       else "in the matrix phase", "lds_reads": reads, "waves_per_simd": waves,
+                       "ns_per_block_per_simd": round(ns, 1), "cycles_per_block_of_a_wavefront": round(cyc, 1),
+                       "mfma_tflops_chip": round(8 * 2 * 32 * 32 * 16 * N_SIMD / ns / 1e3, 1)}
+                rows.append(rec)
+                print(json.dumps(rec), flush=True)
     return rows
 
 
