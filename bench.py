@@ -33,7 +33,7 @@ MFMA_BF16_PEAK_TFLOPS = 2500.0   # MI355X dense bf16, published
 # HBM/fabric bytes per launch from rocprofv3 counter runs (FETCH_SIZE + WRITE_SIZE, each scaled by what
 # the same counter reads for a plain 1 GiB device copy: x2.00 and x1.00; see profiles/).  They hold for
 # the kernel sources with the hash below; with other sources the bench line carries null.
-TRAFFIC_SOURCES_SHA256 = "d6d84a6e2c23402829acc8b19ff0c46099659cc391b4ec8a6d7f0a3061044e99"
+TRAFFIC_SOURCES_SHA256 = "39f81de1bce478a69b42e703e25d685277851c6381e0111e8946276781ab65ab"
 TRAFFIC_BYTES = {
     "long": {"projection": int((2 * 589960 + 196640) * 1024), "attention": int((2 * 151010 + 65792) * 1024)},
     "causal": {"projection": int((2 * 39037 + 36896) * 1024), "attention": int((2 * 18670 + 12480) * 1024)},
@@ -41,14 +41,17 @@ TRAFFIC_BYTES = {
 
 
 def kernel_sources_sha256() -> str:
+    """Hash of what libattnring.so is built from (the probe library's source is not part of it)."""
     import glob
     import hashlib
+    from paper_2012_01114_amd import build as libbuild
+    csrc = os.path.join(ROOT, "paper_2012_01114_amd", "csrc")
+    files = sorted([os.path.join(csrc, f) for f in libbuild.SOURCES] + glob.glob(os.path.join(csrc, "*.h")))
     h = hashlib.sha256()
-    for f in sorted(glob.glob(os.path.join(ROOT, "paper_2012_01114_amd", "csrc", "*"))):
-        if f.endswith((".hip", ".h")):
-            h.update(os.path.basename(f).encode())
-            with open(f, "rb") as fh:
-                h.update(fh.read())
+    for f in files:
+        h.update(os.path.basename(f).encode())
+        with open(f, "rb") as fh:
+            h.update(fh.read())
     return h.hexdigest()
 METRIC = "useful attention TFLOP/s (post-skip) + % bf16 MFMA peak, 1 MI355X"
 
